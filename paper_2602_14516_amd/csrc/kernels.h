@@ -1,0 +1,46 @@
+// Kernel parameter blocks and launcher declarations shared by kernels.hip and api.cpp.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "plan.h"
+
+namespace ampd {
+
+enum : int { KV_BF16 = 0, KV_FP8 = 1 };
+
+struct AttnParams {
+    const void* q;             // bf16 [sum L][Hq][D]
+    void* out;                 // bf16 [sum L][Hq][D]
+    const void* k_pool;        // [pages][Hkv][P][D]
+    const void* v_pool;
+    const float* k_scale;      // [pages][Hkv] (8-bit cache) or null
+    const float* v_scale;
+    const int32_t* block_table;
+    const ReqInfo* reqs;
+    const Item* items;
+    const CombItem* combs;
+    float* partial;
+    int32_t Hq, Hkv, P, logP, max_pages;
+    float c_log2;              // softmax_scale * log2(e)
+};
+
+constexpr int APPEND_MAX_REQS = 128;   // requests per append launch (lengths travel as kernel arguments)
+
+struct AppendParams {
+    const void* k_new;         // bf16 [sum L][Hkv][D]
+    const void* v_new;
+    void* k_pool;
+    void* v_pool;
+    float* k_scale;
+    float* v_scale;
+    const int32_t* block_table;
+    int32_t Hkv, D, P, logP, max_pages, req0;
+    int32_t C[APPEND_MAX_REQS], L[APPEND_MAX_REQS], row_off[APPEND_MAX_REQS];
+};
+
+hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st);
+hipError_t launch_combine(const AttnParams& p, int D, int ncombs, hipStream_t st);
+hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);
+
+}  // namespace ampd

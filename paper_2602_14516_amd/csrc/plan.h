@@ -1,0 +1,73 @@
+// Host-side work planner: cuts a batch of (C_r, L_r) rows into GPU work items.
+//
+// A prefill task is described to the scheduler by its history length and incremental
+// length only (paper Section 3, T_pre(l_hist, l_incr)); a decode step by one token per
+// request (T_dec).  From these lengths alone the planner derives, per request and KV head:
+//   * wide items   -- tiles of up to 128 query rows (tokens x grouped heads) whose 4 waves
+//                     share K/V tiles staged in LDS (compute-bound prefill work), and
+//   * narrow items -- blocks of at most 32 query rows (decode rows, very short chunks)
+//                     whose 4 waves split the key range (bandwidth-bound work),
+// optionally cutting an item's key range into pieces (split-KV) that a combine pass merges.
+// Everything is computed from logical positions, never from physical page ids, so results
+// are bitwise independent of where pages live in the pool.
+#pragma once
+#include <cstdint>
+#include <vector>
+
+namespace ampd {
+
+enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1 };
+
+struct ReqInfo {          // 16 B, one per request, device-visible
+    int32_t C, L, row_off, pad;
+};
+
+struct Item {             // 32 B, one per attention workgroup, device-visible
+    int32_t req;
+    int32_t heads;        // kvh | g0 << 8 | gn << 16 | kind << 24
+    int32_t q0, nq;       // first new-token index and token count of this item
+    int32_t kv_begin, kv_end;   // key range [begin, end) in logical positions
+    int32_t part_off;     // float offset of this item's partial slot, or -1: write final output
+    int32_t pad;
+};
+
+struct CombItem {         // 32 B, one per query tile whose key range was split
+    int32_t req;
+    int32_t heads;
+    int32_t q0, nq;
+    int32_t part_off;     // float offset of split 0
+    int32_t nsplit;
+    int32_t part_stride;  // floats between consecutive splits
+    int32_t pad;
+};
+
+inline int32_t pack_heads(int kvh, int g0, int gn, int kind) {
+    return kvh | (g0 << 8) | (gn << 16) | (kind << 24);
+}
+
+struct Shape {
+    int Hq, Hkv, D, P;
+};
+
+struct PlanOptions {
+    int force_kv_splits = 0;
+    int wg_slots = 512;   // workgroups resident at once: 256 CUs x 2
+};
+
+struct Plan {
+    std::vector<ReqInfo> reqs;
+    std::vector<Item> items;
+    std::vector<CombItem> combs;
+    int64_t num_wide = 0, num_narrow = 0;
+    int64_t partial_floats = 0;
+    int64_t sum_L = 0;
+    // byte layout of the device copy: [reqs][items][combs], each 256 B aligned
+    int64_t off_reqs = 0, off_items = 0, off_combs = 0, plan_bytes = 0;
+    int64_t off_partial = 0, total_bytes = 0;
+};
+
+// ctx_len / incr_len must already be validated (non-negative, no overflow).
+void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int32_t* incr_len,
+                const PlanOptions& opt, Plan& out);
+
+}  // namespace ampd

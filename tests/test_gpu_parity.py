@@ -1,0 +1,131 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_14516_amd as A
+import workloads as W
+from gpu_util import DevBatch, compare, from_dev_bits, sample_rows, TOL_BF16
+
+pytestmark = pytest.mark.gpu
+
+
+def run_attn(db, fn=A.incr_prefill_attn, **kw):
+    b = db.b
+    out = fn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new,
+             block_table_host=b.block_table, **kw)
+    torch.cuda.synchronize()
+    return from_dev_bits(out)
+
+
+def check_append(db):
+    b = db.b
+    k_ref, v_ref = oracle.kv_append_reference(b.k_pool, b.v_pool, b.block_table, b.ctx_len, b.incr_len,
+                                              b.k_new, b.v_new, b.P)
+    assert np.array_equal(from_dev_bits(db.k_pool), k_ref), "K pool differs from the append reference"
+    assert np.array_equal(from_dev_bits(db.v_pool), v_ref), "V pool differs from the append reference"
+
+
+def test_config1_full():
+    print("case: config 1", flush=True)
+    db = DevBatch(W.make_config(1, poison=True))
+    out = run_attn(db)
+    check_append(db)
+    mx, mean = compare(db.b, out, label="cfg1")
+    print(f"cfg1 max-abs {mx:.2e} mean-abs {mean:.2e}")
+
+
+@pytest.mark.parametrize("name,C,L,Hq,Hkv,d,P", [
+    ("ragged-d128", [0, 1, 15, 16, 17, 100, 257, 64], [1, 7, 33, 64, 129, 5, 70, 200], 8, 2, 128, 16),
+    ("ragged-d64", [0, 3, 31, 200], [65, 1, 40, 130], 8, 2, 64, 16),
+    ("gqa8-p32", [300, 0, 77], [150, 31, 1], 16, 2, 128, 32),
+    ("mha", [50, 129], [140, 9], 4, 4, 128, 16),
+    ("gqa16-p64", [130, 5], [3, 70], 32, 2, 64, 64),
+    ("decode-only", [1, 15, 16, 63, 64, 65, 1000, 2500], [1] * 8, 16, 2, 128, 16),
+    ("empty-rows", [10, 0, 20], [0, 5, 0], 8, 2, 128, 16),
+])
+def test_small_shapes_elementwise(name, C, L, Hq, Hkv, d, P):
+    print(f"case: {name}", flush=True)
+    db = DevBatch(W.make_batch(C, L, Hq, Hkv, d, P, seed=hash(name) % 10000, poison=True, name=name))
+    out = run_attn(db)
+    check_append(db)
+    compare(db.b, out, label=name)
+
+
+@pytest.mark.parametrize("splits", [2, 3, 7])
+def test_forced_kv_splits_match(splits):
+    print(f"case: forced splits {splits}", flush=True)
+    b = W.make_batch([0, 500, 1025, 64, 3000], [300, 1, 77, 2, 1], 8, 2, 128, 16, seed=21, poison=True)
+    db = DevBatch(b)
+    out = run_attn(db, force_kv_splits=splits)
+    compare(b, out, label=f"splits{splits}")
+
+
+def test_mixed_equals_separate_sub_batches():
+    print("case: mixed vs separate", flush=True)
+    C = [700, 90, 2048, 5, 300, 1500]
+    L = [1, 260, 1, 1, 40, 1]
+    b = W.make_batch(C, L, 16, 2, 128, 16, seed=31, poison=True)
+    db = DevBatch(b)
+    mixed = run_attn(db, fn=A.mixed_batch_attn)
+    check_append(db)
+    compare(b, mixed, label="mixed")
+    # the rows of a mixed batch equal the rows of running each row alone
+    off = b.row_offsets
+    for r in range(len(C)):
+        sub = W.Batch(b.Hq, b.Hkv, b.d, b.P, b.scale, b.ctx_len[r:r + 1], b.incr_len[r:r + 1],
+                      b.block_table[r:r + 1], b.num_pages, b.k_pool, b.v_pool,
+                      b.q[off[r]:off[r + 1]], b.k_new[off[r]:off[r + 1]], b.v_new[off[r]:off[r + 1]])
+        o = run_attn(DevBatch(sub), fn=A.mixed_batch_attn)
+        assert np.array_equal(o, mixed[off[r]:off[r + 1]]), f"row {r} differs between mixed and single-row launch"
+
+
+def test_page_permutation_is_bitwise_invariant_and_relaunch_idempotent():
+    print("case: permutation", flush=True)
+    C, L = [333, 40, 1200], [70, 1, 5]
+    b1 = W.make_batch(C, L, 8, 2, 128, 16, seed=41, poison=True)
+    db1 = DevBatch(b1)
+    o1 = run_attn(db1)
+    o1b = run_attn(db1)                       # same call again: append and attention are idempotent
+    assert np.array_equal(o1, o1b)
+    # same logical content, other physical pages, bigger pool
+    n2 = b1.num_pages + 37
+    perm = np.random.default_rng(5).permutation(n2).astype(np.int32)
+    k2 = np.full((n2,) + b1.k_pool.shape[1:], W.NAN_BF16, np.uint16)
+    v2 = k2.copy()
+    bt2 = np.full_like(b1.block_table, -1)
+    i = 0
+    for r in range(b1.num_reqs):
+        for c in range(b1.block_table.shape[1]):
+            if b1.block_table[r, c] >= 0:
+                bt2[r, c] = perm[i]; i += 1
+                k2[bt2[r, c]] = b1.k_pool[b1.block_table[r, c]]
+                v2[bt2[r, c]] = b1.v_pool[b1.block_table[r, c]]
+    b2 = W.Batch(b1.Hq, b1.Hkv, b1.d, b1.P, b1.scale, b1.ctx_len, b1.incr_len, bt2, n2, k2, v2, b1.q, b1.k_new, b1.v_new)
+    o2 = run_attn(DevBatch(b2))
+    assert np.array_equal(o1, o2)
+
+
+def test_append_alone_is_bit_exact_and_touches_nothing_else():
+    print("case: append alone", flush=True)
+    b = W.make_batch([0, 5, 16, 100, 31], [40, 1, 16, 3, 0], 8, 4, 128, 16, seed=51, poison=True)
+    db = DevBatch(b)
+    A.kv_append(db.cache, b.ctx_len, b.incr_len, db.bt, db.k_new, db.v_new, block_table_host=b.block_table)
+    torch.cuda.synchronize()
+    check_append(db)
+    # attention-only over the appended pool equals append-then-attend
+    o = A.paged_attn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q)
+    torch.cuda.synchronize()
+    compare(b, from_dev_bits(o), label="append+paged_attn")
+
+
+def test_shrunk_config_shapes():
+    for k, s in ((2, 8), (3, 16), (4, 32)):
+        print(f"case: cfg{k}/s{s}", flush=True)
+        b = W.make_config(k, shrink=s, poison=True)
+        db = DevBatch(b)
+        out = run_attn(db, fn=A.mixed_batch_attn if k == 3 else A.incr_prefill_attn)
+        rows = sample_rows(b, 6, seed=k)
+        mx, mean = compare(b, out, rows=rows, label=b.name)
+        print(f"{b.name} max-abs {mx:.2e} mean-abs {mean:.2e}")

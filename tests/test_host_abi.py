@@ -1,0 +1,120 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every declared symbol, validates
+arguments on the host, and its work planner covers every causal (query, key) pair exactly once."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2602_14516_amd as A
+import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_symbol_declared_in_the_header():
+    hdr = open(os.path.join(ROOT, "include", "ampd.h")).read()
+    hdr = re.sub(r"/\*.*?\*/", "", hdr, flags=re.S)
+    declared = set(re.findall(r"\b(ampd_[a-z_0-9]+)\s*\(", hdr))
+    assert declared == set(A.EXPORTED_SYMBOLS)
+    for name in declared:
+        assert hasattr(A.lib, name), name
+    assert "gfx950" in A.version()
+    assert A.status_string(0) == "ok" and "range" in A.status_string(-4)
+
+
+def shape_cache(Hq=8, Hkv=2, d=128, P=16, scale=0.1, pages=1000):
+    c = A.KVCache(Hq, Hkv, d, P, None, None, scale)
+    c.num_pages_hint = pages
+    return c
+
+
+def test_host_validation_rejects_bad_arguments_without_a_gpu():
+    ok = A.workspace_bytes(shape_cache(), [10], [5], 1)
+    assert ok >= 256
+    assert A.workspace_bytes(shape_cache(Hq=7), [10], [5], 1) == 0          # Hq % Hkv
+    assert A.workspace_bytes(shape_cache(d=96), [10], [5], 1) == 0          # head_dim
+    assert A.workspace_bytes(shape_cache(P=8), [10], [5], 1) == 0           # page size
+    assert A.workspace_bytes(shape_cache(scale=0.0), [10], [5], 1) == 0     # scale
+    assert A.workspace_bytes(shape_cache(), [-1], [5], 1) == 0              # negative length
+    assert A.workspace_bytes(shape_cache(), [10], [7], 1) == 0              # table too narrow: 17 tokens
+    assert A.workspace_bytes(shape_cache(), [10], [0], 0) >= 256            # L = 0 rows need no pages
+    with pytest.raises(A.AmpdError) as e:
+        A.plan_describe(shape_cache(d=96), [10], [5], 1)
+    assert e.value.status == -2
+    # entry points refuse NULL pools / tables before touching the GPU
+    c = shape_cache()
+    with pytest.raises(A.AmpdError) as e:
+        A.kv_append(c, [10], [5], None, None, None, stream=0)
+    assert e.value.status == -1
+
+
+def test_page_range_check_uses_the_host_mirror():
+    # host-only call path: ampd_kv_append validates the mirror before anything else that needs a GPU
+    c = shape_cache(pages=4)
+    b = A.binding
+    batch, keep = b._batch([0], [20], None, np.array([[0, 9]], np.int32), max_pages=2)
+    batch.d_block_table = 8          # any non-NULL address: validation must fail before it is used
+    cs = c.c_struct()
+    cs.k_pool = cs.v_pool = 8
+    st = A.lib.ampd_kv_append(ctypes.byref(cs), ctypes.byref(batch), 8, 8, None)
+    assert st == -4
+
+
+def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
+    c = shape_cache(Hq, Hkv, d, P)
+    mp = int(max(1, ((np.array(C) + np.array(L) + P - 1) // P).max()))
+    items = A.plan_items(c, C, L, mp, force_kv_splits=splits)
+    G = Hq // Hkv
+    ranges = {}
+    for req, kind, kvh, g0, gn, q0, nq, kb, ke, po in items.tolist():
+        assert 0 < gn <= 32 and g0 + gn <= G and nq > 0 and kb < ke and kb % 64 == 0
+        assert nq * gn <= (128 if kind == 0 else 32)
+        for g in range(g0, g0 + gn):
+            for i in range(q0, q0 + nq):
+                ranges.setdefault((req, kvh * G + g, i), []).append((kb, ke))
+    for r in range(len(C)):
+        for h in range(Hq):
+            for i in range(L[r]):
+                rs = sorted(ranges.pop((r, h, i)))
+                vis = C[r] + i + 1
+                pos = 0
+                for kb, ke in rs:
+                    assert kb == pos, f"gap/overlap at request {r} head {h} query {i}: {rs}"
+                    pos = ke
+                assert pos >= vis and rs[-1][0] < vis or len(rs) == 1 or rs[-1][0] < C[r] + L[r]
+                assert pos >= vis
+    assert not ranges, "items refer to queries that do not exist"
+    return items
+
+
+@pytest.mark.parametrize("splits", [0, 2, 5])
+def test_planner_covers_every_causal_pair_exactly_once(splits):
+    rng = np.random.default_rng(splits)
+    for Hq, Hkv, d, P in [(8, 2, 128, 16), (4, 4, 64, 32), (6, 2, 128, 16), (64, 1, 128, 16), (8, 1, 128, 32)]:
+        C = rng.integers(0, 700, size=5).tolist()
+        L = rng.integers(0, 90, size=5).tolist()
+        L[0] = 1
+        C[1] = 0
+        coverage_check(Hq, Hkv, d, P, C, L, splits)
+
+
+def test_planner_kinds_and_split_policy():
+    c = shape_cache(64, 8, 128, 16)
+    C, L = W.config_lengths(3)
+    mp = int(((C.astype(int) + L + 15) // 16).max())
+    info = A.plan_describe(c, C, L, mp)
+    # 96 decode rows x 8 KV heads are narrow and split; prefill rows are wide and unsplit
+    assert info["num_combine_items"] == 96 * 8
+    assert info["num_narrow_items"] > 4 * 96 * 8
+    assert info["num_wide_items"] == sum(8 * -(-int(l) // 16) for l in L if l > 1)
+    assert A.workspace_bytes(c, C, L, mp) == info["plan_bytes"] + -(-info["partial_bytes"] // 256) * 256
+    # the order of the work list depends on lengths only (needed for bitwise page-permutation invariance)
+    a = A.plan_items(c, C, L, mp)
+    b = A.plan_items(c, C, L, mp)
+    assert np.array_equal(a, b)
+    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
+    wide = a[:, 1] == 0
+    cost = np.where(wide, 4 * keys, keys)
+    assert np.all(np.diff(cost) <= 0)            # longest first
