@@ -1,4 +1,6 @@
 """GPU parity: the HIP path through the C ABI against the fp64 oracle, element by element."""
+import zlib
+
 import numpy as np
 import pytest
 import torch
@@ -47,7 +49,7 @@ def test_config1_full():
 ])
 def test_small_shapes_elementwise(name, C, L, Hq, Hkv, d, P):
     print(f"case: {name}", flush=True)
-    db = DevBatch(W.make_batch(C, L, Hq, Hkv, d, P, seed=hash(name) % 10000, poison=True, name=name))
+    db = DevBatch(W.make_batch(C, L, Hq, Hkv, d, P, seed=zlib.crc32(name.encode()) % 10000, poison=True, name=name))
     out = run_attn(db)
     check_append(db)
     compare(db.b, out, label=name)
