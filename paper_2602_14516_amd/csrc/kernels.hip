@@ -67,8 +67,9 @@ template <>
 struct RawChunk<KV_BF16> {
     u32x4 v;
     __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
-    __device__ __forceinline__ void load(const void* base, int64_t elem_off) {
-        v = *reinterpret_cast<const u32x4*>(static_cast<const char*>(base) + elem_off * 2);
+    static constexpr int ES = 2;                      // bytes per stored element
+    __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
+        v = *reinterpret_cast<const u32x4*>(base + lane_off);
     }
     __device__ __forceinline__ u32x4 widen(float) const { return v; }
 };
@@ -76,8 +77,9 @@ template <>
 struct RawChunk<KV_FP8> {
     u32x2 v;
     __device__ __forceinline__ void zero() { v = u32x2{0, 0}; }
-    __device__ __forceinline__ void load(const void* base, int64_t elem_off) {
-        v = *reinterpret_cast<const u32x2*>(static_cast<const char*>(base) + elem_off);
+    static constexpr int ES = 1;
+    __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
+        v = *reinterpret_cast<const u32x2*>(base + lane_off);
     }
     // decode(code) * scale is exact in bf16: 4 significant bits times a power of two
     __device__ __forceinline__ u32x4 widen(float scale) const {
@@ -212,10 +214,69 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const ItemCtx& ic, i
     }
 }
 
-// Physical page of logical key `key` (wave-uniform argument -> scalar load).
-__device__ __forceinline__ int page_of(const AttnParams& p, const ItemCtx& ic, int key) {
-    return ic.bt_row[key >> p.logP];
-}
+// Cooperative K/V tile loader: NTHR threads move NKEYS consecutive keys (K and V rows) from the
+// paged pools into registers and then into LDS.  Page ids are fetched one tile earlier than
+// the K/V rows they address, so that the dependent block-table -> pool load chain is never on
+// the critical path.  Within one pass a wave reads 64/CPK consecutive keys of one page, so
+// the page id is wave-uniform: it is moved to a scalar register and the 64-bit address
+// arithmetic runs on the scalar unit; the per-lane part of the address is a constant.
+template <int D, int KVT, int NTHR, int NKEYS>
+struct Loader {
+    static constexpr int CPK = D / 8;                 // 8-element chunks per key row
+    static constexpr int KPP = NTHR / CPK;            // keys per pass
+    static constexpr int NPASS = NKEYS / KPP;
+    static constexpr int KPW = 64 / CPK;              // keys per wave per pass
+    static constexpr int ES = RawChunk<KVT>::ES;
+    int pg[NPASS];
+    RawChunk<KVT> k[NPASS], v[NPASS];
+    float ks[NPASS], vs[NPASS];
+
+    // t: thread index inside the group of NTHR threads
+    __device__ __forceinline__ void fetch_pages(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int key0 = kbase + ps * KPP + (t >> 6) * KPW;
+            pg[ps] = key0 < ic.kv_end ? ic.bt_row[key0 >> p.logP] : 0;
+        }
+    }
+
+    __device__ __forceinline__ void fetch_kv(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+        const uint32_t lane_off = (uint32_t)(((t & 63) / CPK) * D + (t % CPK) * 8) * ES;
+        const bool full = kbase + NKEYS <= ic.kv_end;           // uniform
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int key0 = __builtin_amdgcn_readfirstlane(kbase + ps * KPP + (t >> 6) * KPW);
+            const int page = __builtin_amdgcn_readfirstlane(pg[ps]);
+            const int64_t row = ((((int64_t)page * p.Hkv + ic.kvh) << p.logP) + (key0 & (p.P - 1))) * D * ES;
+            const char* kb = static_cast<const char*>(p.k_pool) + row;
+            const char* vb = static_cast<const char*>(p.v_pool) + row;
+            ks[ps] = 1.0f;
+            vs[ps] = 1.0f;
+            if (full || key0 + (t & 63) / CPK < ic.kv_end) {
+                k[ps].load(kb, lane_off);
+                v[ps].load(vb, lane_off);
+                if (KVT == KV_FP8) {
+                    ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
+                    vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
+                }
+            } else {
+                k[ps].zero();                                    // keys past the item's end: zeros, so
+                v[ps].zero();                                    // that 0-weights never meet NaN garbage
+            }
+        }
+    }
+
+    // kl / vl: LDS byte addresses of key 0 of this tile's K and V rows
+    __device__ __forceinline__ void commit(uint32_t kl, uint32_t vl, int t) const {
+        const int ch = t % CPK;
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const int kloc = ps * KPP + t / CPK;
+            *LDS_PTR(u32x4, kl + kloc * Geo<D>::KSTR + ch * 16) = k[ps].widen(ks[ps]);
+            *LDS_PTR(u32x4, vl + kloc * Geo<D>::VSTR + ch * 16) = v[ps].widen(vs[ps]);
+        }
+    }
+};
 
 // Final write of one wave's O^T: either bf16 output rows or fp32 partials.
 //   row_in_item: this lane's row index inside the item (token_local * gn + head) or -1
@@ -262,57 +323,6 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
 // wide body: 4 waves x 32 query rows share 64-key K/V tiles, double-buffered in LDS
 
 template <int D, int KVT>
-struct WideStage {
-    static constexpr int NPASS = 64 * Geo<D>::CPK / WG;     // chunks per thread per tile (4 for d=128)
-    RawChunk<KVT> k[NPASS], v[NPASS];
-    float ks[NPASS], vs[NPASS];
-};
-
-template <int D, int KVT>
-__device__ __forceinline__ void wide_fetch(const AttnParams& p, const ItemCtx& ic, int kbase, int tid,
-                                           WideStage<D, KVT>& rg) {
-    using G_ = Geo<D>;
-    constexpr int KPP = WG / G_::CPK;                 // keys per pass
-    constexpr int KPW = 64 / G_::CPK;                 // keys per wave per pass (within one page)
-    const int wave = tid >> 6;
-    const int ch = tid % G_::CPK;
-#pragma unroll
-    for (int ps = 0; ps < WideStage<D, KVT>::NPASS; ++ps) {
-        const int key0 = __builtin_amdgcn_readfirstlane(kbase + ps * KPP + wave * KPW);   // wave-uniform
-        const int key = kbase + ps * KPP + tid / G_::CPK;
-        rg.k[ps].zero();
-        rg.v[ps].zero();
-        rg.ks[ps] = 1.0f;
-        rg.vs[ps] = 1.0f;
-        if (key0 < ic.kv_end) {
-            const int page = page_of(p, ic, key0);
-            if (key < ic.kv_end) {
-                const int64_t e = ((((int64_t)page * p.Hkv + ic.kvh) << p.logP) + (key & (p.P - 1))) * D + ch * 8;
-                rg.k[ps].load(p.k_pool, e);
-                rg.v[ps].load(p.v_pool, e);
-                if (KVT == KV_FP8) {
-                    rg.ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
-                    rg.vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
-                }
-            }
-        }
-    }
-}
-
-template <int D, int KVT>
-__device__ __forceinline__ void wide_commit(uint32_t stage, int tid, const WideStage<D, KVT>& rg) {
-    using G_ = Geo<D>;
-    constexpr int KPP = WG / G_::CPK;
-    const int ch = tid % G_::CPK;
-#pragma unroll
-    for (int ps = 0; ps < WideStage<D, KVT>::NPASS; ++ps) {
-        const int kl = ps * KPP + tid / G_::CPK;          // 0..63
-        *LDS_PTR(u32x4, stage + kl * G_::KSTR + ch * 16) = rg.k[ps].widen(rg.ks[ps]);
-        *LDS_PTR(u32x4, stage + 2 * G_::K32 + kl * G_::VSTR + ch * 16) = rg.v[ps].widen(rg.vs[ps]);
-    }
-}
-
-template <int D, int KVT>
 __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
     using G_ = Geo<D>;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -338,15 +348,20 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
 
     const int k_lo = ic.kv_begin;                          // multiple of 64
     const int ntiles = (ic.kv_end - k_lo + 63) >> 6;
-    WideStage<D, KVT> rg;
-    wide_fetch<D, KVT>(p, ic, k_lo, tid, rg);
-    wide_commit<D, KVT>(smem, tid, rg);
+    Loader<D, KVT, WG, 64> ld;
+    ld.fetch_pages(p, ic, k_lo, tid);
+    ld.fetch_kv(p, ic, k_lo, tid);
+    if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + 64, tid);
+    ld.commit(smem, smem + 2 * G_::K32, tid);
     __syncthreads();
     for (int t = 0; t < ntiles; ++t) {
         const uint32_t cur = smem + (t & 1) * G_::WIDE_STAGE;
         const uint32_t nxt = smem + ((t + 1) & 1) * G_::WIDE_STAGE;
         const bool more = t + 1 < ntiles;
-        if (more) wide_fetch<D, KVT>(p, ic, k_lo + (t + 1) * 64, tid, rg);
+        if (more) {
+            ld.fetch_kv(p, ic, k_lo + (t + 1) * 64, tid);
+            if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * 64, tid);
+        }
         if (wave_active) {
 #pragma unroll
             for (int kb = 0; kb < 2; ++kb) {
@@ -361,7 +376,7 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
                     block32<D, false>(kl, vl, Q, st, p.c_log2, rel, lane);
             }
         }
-        if (more) wide_commit<D, KVT>(nxt, tid, rg);
+        if (more) ld.commit(nxt, nxt + 2 * G_::K32, tid);
         __syncthreads();
     }
     store_result<D>(p, ic, st, tok, hg, valid ? tok_local * ic.gn + hg : -1, lane);
@@ -370,55 +385,6 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
 // ---------------------------------------------------------------------------------------------
 // narrow body: <= 32 query rows; the 4 waves take 32-key blocks round-robin, each through its
 // own LDS region, and merge their (m, l, O) through LDS at the end
-
-template <int D, int KVT>
-struct NarrowStage {
-    static constexpr int NPASS = 32 * Geo<D>::CPK / 64;     // 8 for d=128
-    RawChunk<KVT> k[NPASS], v[NPASS];
-    float ks[NPASS], vs[NPASS];
-};
-
-template <int D, int KVT>
-__device__ __forceinline__ void narrow_fetch(const AttnParams& p, const ItemCtx& ic, int kbase, int lane,
-                                             NarrowStage<D, KVT>& rg) {
-    using G_ = Geo<D>;
-    constexpr int KPP = 64 / G_::CPK;                 // keys per pass (4 for d=128), inside one page
-    const int ch = lane % G_::CPK;
-#pragma unroll
-    for (int ps = 0; ps < NarrowStage<D, KVT>::NPASS; ++ps) {
-        const int key0 = kbase + ps * KPP;            // wave-uniform
-        const int key = key0 + lane / G_::CPK;
-        rg.k[ps].zero();
-        rg.v[ps].zero();
-        rg.ks[ps] = 1.0f;
-        rg.vs[ps] = 1.0f;
-        if (key0 < ic.kv_end) {
-            const int page = page_of(p, ic, key0);
-            if (key < ic.kv_end) {
-                const int64_t e = ((((int64_t)page * p.Hkv + ic.kvh) << p.logP) + (key & (p.P - 1))) * D + ch * 8;
-                rg.k[ps].load(p.k_pool, e);
-                rg.v[ps].load(p.v_pool, e);
-                if (KVT == KV_FP8) {
-                    rg.ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
-                    rg.vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
-                }
-            }
-        }
-    }
-}
-
-template <int D, int KVT>
-__device__ __forceinline__ void narrow_commit(uint32_t kl, uint32_t vl, int lane, const NarrowStage<D, KVT>& rg) {
-    using G_ = Geo<D>;
-    constexpr int KPP = 64 / G_::CPK;
-    const int ch = lane % G_::CPK;
-#pragma unroll
-    for (int ps = 0; ps < NarrowStage<D, KVT>::NPASS; ++ps) {
-        const int kloc = ps * KPP + lane / G_::CPK;
-        *LDS_PTR(u32x4, kl + kloc * G_::KSTR + ch * 16) = rg.k[ps].widen(rg.ks[ps]);
-        *LDS_PTR(u32x4, vl + kloc * G_::VSTR + ch * 16) = rg.v[ps].widen(rg.vs[ps]);
-    }
-}
 
 template <int D, int KVT>
 __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
@@ -442,12 +408,19 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
     const uint32_t kl = smem + wave * (G_::K32 + G_::V32);
     const uint32_t vl = kl + G_::K32;
     const int nblocks = (ic.kv_end - ic.kv_begin + 31) >> 5;
-    NarrowStage<D, KVT> rg;
-    if (wave < nblocks) narrow_fetch<D, KVT>(p, ic, ic.kv_begin + wave * 32, lane, rg);
+    Loader<D, KVT, 64, 32> ld;
+    if (wave < nblocks) {
+        ld.fetch_pages(p, ic, ic.kv_begin + wave * 32, lane);
+        ld.fetch_kv(p, ic, ic.kv_begin + wave * 32, lane);
+        if (wave + 4 < nblocks) ld.fetch_pages(p, ic, ic.kv_begin + (wave + 4) * 32, lane);
+    }
     for (int b = wave; b < nblocks; b += 4) {
         const int kbase = ic.kv_begin + b * 32;
-        narrow_commit<D, KVT>(kl, vl, lane, rg);
-        if (b + 4 < nblocks) narrow_fetch<D, KVT>(p, ic, kbase + 128, lane, rg);
+        ld.commit(kl, vl, lane);
+        if (b + 4 < nblocks) {
+            ld.fetch_kv(p, ic, kbase + 128, lane);
+            if (b + 8 < nblocks) ld.fetch_pages(p, ic, kbase + 256, lane);
+        }
         const int rel = lim - kbase - 4 * (lane >> 5);
         if (kbase + 31 > first_lim)
             block32<D, true>(kl, vl, Q, st, p.c_log2, rel, lane);
