@@ -132,38 +132,55 @@ struct WaveAcc {
     float l;      // this lane's share of the running sum (lanes l and l^32 hold halves)
 };
 
-// One 32-key block: S^T = K Q^T, online softmax, O^T += V^T P^T.
-//   kl / vl: LDS addresses (bytes) of the block's K and V rows
-//   rel:     per lane, (last visible key of this lane's query) - (first key of the block) - 4*(lane/32)
-template <int D, bool MASK>
-__device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK],
-                                        WaveAcc<D>& st, float c, int rel, int lane) {
+// NB consecutive 32-key blocks: S^T = K Q^T, online softmax, O^T += V^T P^T.
+//   kl / vl:  LDS addresses (bytes) of the first block's K and V rows; block j follows at
+//             kl + j*kstep / vl + j*vstep
+//   rel:      per lane, (last visible key of this lane's query) - (first key of block 0) - 4*(lane/32)
+//   mask_from: first block index that needs the causal select (NB: none); wave-uniform
+// The running maximum is a *reference* m, not the exact maximum: it is raised (and O, l
+// rescaled) only when some row's block maximum exceeds it by more than RESCALE_SLACK in the
+// log2 domain, so that probabilities stay below 2^RESCALE_SLACK.  (m, l, O) remain a
+// consistent triple, which is all the final normalisation and the split-KV merge need.
+constexpr float RESCALE_SLACK = 8.0f;
+
+template <int D, int NB>
+__device__ __forceinline__ void blocks(uint32_t kl, uint32_t vl, int kstep, int vstep,
+                                       const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st, float c, int rel,
+                                       int mask_from, int lane) {
     using G_ = Geo<D>;
     const int g = lane >> 5;
-    f32x16 S = {0};
-    {
-        const uint32_t ka = kl + (lane & 31) * G_::KSTR + g * 16;
+    f32x16 S[NB];
+    const uint32_t ka = kl + (lane & 31) * G_::KSTR + g * 16;
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        S[j] = f32x16{0};
 #pragma unroll
         for (int kk = 0; kk < G_::NKK; ++kk) {
-            const u32x4 raw = *LDS_PTR(const u32x4, ka + kk * 32);
-            S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), Q[kk], S, 0, 0, 0);
+            const u32x4 raw = *LDS_PTR(const u32x4, ka + j * kstep + kk * 32);
+            S[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), Q[kk], S[j], 0, 0, 0);
         }
     }
-    if (MASK) {
+    if (mask_from < NB) {                              // wave-uniform: only blocks crossing the diagonal
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const int koff = (i >> 2) * 8 + (i & 3);
-            S[i] = koff <= rel ? S[i] : NEG_INF;
+        for (int j = 0; j < NB; ++j) {
+            if (j >= mask_from) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int koff = j * 32 + (i >> 2) * 8 + (i & 3);
+                    S[j][i] = koff <= rel ? S[j][i] : NEG_INF;
+                }
+            }
         }
     }
-    float mx = S[0];
+    float mx = S[0][0];
 #pragma unroll
-    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[i]);
-    mx = fmaxf(mx, xor32(mx));
-    const float m_new = fmaxf(st.m, mx * c);
-    const float m_use = m_new == NEG_INF ? 0.0f : m_new;
-    if (__any(m_new > st.m)) {                       // wave-uniform: rescale only when some max moved
-        const float alpha = fast_exp2(st.m - m_use);
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int i = (j == 0 ? 1 : 0); i < 16; ++i) mx = fmaxf(mx, S[j][i]);
+    mx = fmaxf(mx, xor32(mx)) * c;
+    if (__any(mx > st.m + RESCALE_SLACK)) {            // rare after the first blocks
+        const float m_new = fmaxf(st.m, mx);
+        const float alpha = fast_exp2(st.m - (m_new == NEG_INF ? 0.0f : m_new));
         st.l *= alpha;
 #pragma unroll
         for (int db = 0; db < G_::NDB; ++db)
@@ -171,28 +188,34 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
             for (int i = 0; i < 16; ++i) st.O[db][i] *= alpha;
         st.m = m_new;
     }
+    const float m_use = st.m == NEG_INF ? 0.0f : st.m;
     float psum = 0.0f;
-    bf16x8 Pb[2];
+    bf16x8 Pb[NB][2];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const float pv = fast_exp2(__builtin_fmaf(S[i], c, -m_use));
-        psum += pv;
-        Pb[i >> 3][i & 7] = (__bf16)pv;
-    }
+    for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const float pv = fast_exp2(__builtin_fmaf(S[j][i], c, -m_use));
+            psum += pv;
+            Pb[j][i >> 3][i & 7] = (__bf16)pv;
+        }
     st.l += psum;
-    // second product: k-slot j of MFMA cc is key 16*cc + 8*(j/4) + 4*g + j%4
+    // second product: k-slot s of MFMA cc is key 16*cc + 8*(s/4) + 4*g + s%4 of its block
     const int hi = (lane >> 4) & 1, i16 = lane & 15;
     const uint32_t va = vl + (4 * g + (i16 >> 2)) * G_::VSTR + (hi * 16 + (i16 & 3) * 4) * 2;
+    typedef short s16x8 __attribute__((ext_vector_type(8)));
 #pragma unroll
-    for (int cc = 0; cc < 2; ++cc) {
+    for (int j = 0; j < NB; ++j) {
 #pragma unroll
-        for (int db = 0; db < G_::NDB; ++db) {
-            const uint32_t a0 = va + (16 * cc) * G_::VSTR + db * 64;
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
-            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + 8 * G_::VSTR));
-            typedef short s16x8 __attribute__((ext_vector_type(8)));
-            const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-            st.O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), Pb[cc], st.O[db], 0, 0, 0);
+        for (int cc = 0; cc < 2; ++cc) {
+#pragma unroll
+            for (int db = 0; db < G_::NDB; ++db) {
+                const uint32_t a0 = va + j * vstep + (16 * cc) * G_::VSTR + db * 64;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+                const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + 8 * G_::VSTR));
+                const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+                st.O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), Pb[j][cc], st.O[db], 0, 0, 0);
+            }
         }
     }
 }
@@ -240,9 +263,9 @@ struct Loader {
         }
     }
 
-    __device__ __forceinline__ void fetch_kv(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+    template <bool FULL>
+    __device__ __forceinline__ void fetch_kv_impl(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
         const uint32_t lane_off = (uint32_t)(((t & 63) / CPK) * D + (t % CPK) * 8) * ES;
-        const bool full = kbase + NKEYS <= ic.kv_end;           // uniform
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
             const int key0 = __builtin_amdgcn_readfirstlane(kbase + ps * KPP + (t >> 6) * KPW);
@@ -252,18 +275,25 @@ struct Loader {
             const char* vb = static_cast<const char*>(p.v_pool) + row;
             ks[ps] = 1.0f;
             vs[ps] = 1.0f;
-            if (full || key0 + (t & 63) / CPK < ic.kv_end) {
+            if (KVT == KV_FP8) {
+                ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
+                vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
+            }
+            if (FULL || key0 + (t & 63) / CPK < ic.kv_end) {
                 k[ps].load(kb, lane_off);
                 v[ps].load(vb, lane_off);
-                if (KVT == KV_FP8) {
-                    ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
-                    vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
-                }
             } else {
                 k[ps].zero();                                    // keys past the item's end: zeros, so
                 v[ps].zero();                                    // that 0-weights never meet NaN garbage
             }
         }
+    }
+
+    __device__ __forceinline__ void fetch_kv(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+        if (kbase + NKEYS <= ic.kv_end)                          // uniform: whole tile inside the key range
+            fetch_kv_impl<true>(p, ic, kbase, t);
+        else
+            fetch_kv_impl<false>(p, ic, kbase, t);
     }
 
     // kl / vl: LDS byte addresses of key 0 of this tile's K and V rows
@@ -362,19 +392,12 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
             ld.fetch_kv(p, ic, k_lo + (t + 1) * 64, tid);
             if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * 64, tid);
         }
-        if (wave_active) {
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb) {
-                const int kbase = k_lo + t * 64 + kb * 32;
-                if (kbase > w_last) break;                 // every row of the wave masks this block
-                const uint32_t kl = cur + kb * G_::K32;
-                const uint32_t vl = cur + 2 * G_::K32 + kb * G_::V32;
-                const int rel = lim - kbase - 4 * (lane >> 5);
-                if (kbase + 31 > w_first)
-                    block32<D, true>(kl, vl, Q, st, p.c_log2, rel, lane);
-                else
-                    block32<D, false>(kl, vl, Q, st, p.c_log2, rel, lane);
-            }
+        const int kbase = k_lo + t * 64;
+        if (wave_active && kbase <= w_last) {               // else every row of the wave masks this tile
+            const int rel = lim - kbase - 4 * (lane >> 5);
+            // block j (32 keys) needs the causal select iff its last key is beyond the wave's first limit
+            const int mask_from = kbase + 31 > w_first ? 0 : (kbase + 63 > w_first ? 1 : 2);
+            blocks<D, 2>(cur, cur + 2 * G_::K32, G_::K32, G_::V32, Q, st, p.c_log2, rel, mask_from, lane);
         }
         if (more) ld.commit(nxt, nxt + 2 * G_::K32, tid);
         __syncthreads();
@@ -422,10 +445,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             if (b + 8 < nblocks) ld.fetch_pages(p, ic, kbase + 256, lane);
         }
         const int rel = lim - kbase - 4 * (lane >> 5);
-        if (kbase + 31 > first_lim)
-            block32<D, true>(kl, vl, Q, st, p.c_log2, rel, lane);
-        else
-            block32<D, false>(kl, vl, Q, st, p.c_log2, rel, lane);
+        blocks<D, 1>(kl, vl, 0, 0, Q, st, p.c_log2, rel, kbase + 31 > first_lim ? 0 : 1, lane);
     }
     // merge the four waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
     const float ltot = st.l + xor32(st.l);
