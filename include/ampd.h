@@ -158,8 +158,8 @@ ampd_status ampd_paged_attn(const ampd_kv_cache *cache, const ampd_batch *batch,
  * for the benchmark's roofline accounting).  Returns AMPD_OK or a validation error. */
 typedef struct {
     int64_t num_items;          /* attention work items (= workgroups of the attention launch) */
-    int64_t num_wide_items;     /* prefill tiles: up to 128 query rows, 4 waves share K/V tiles */
-    int64_t num_narrow_items;   /* decode-style items: <= 32 query rows, 4 waves split the keys */
+    int64_t num_wide_items;     /* prefill tiles: up to 256 query rows, 8 waves share K/V tiles */
+    int64_t num_narrow_items;   /* decode-style items: <= 32 query rows, 8 waves split the keys */
     int64_t num_combine_items;  /* query tiles whose key range was split */
     int64_t num_append_launches;
     int64_t partial_bytes;      /* split-KV partial results inside the workspace */

@@ -11,7 +11,7 @@ from dataclasses import dataclass
 
 import numpy as np
 
-LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libampd.so")
+LIB_PATH = os.environ.get("AMPD_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libampd.so")
 
 EXPORTED_SYMBOLS = [
     "ampd_workspace_bytes", "ampd_workspace_bytes_opts", "ampd_kv_append",

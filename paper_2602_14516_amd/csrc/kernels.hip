@@ -15,9 +15,23 @@
 // ONE query row: row max / row sum are in-lane reductions plus one exchange with lane l^32,
 // and the bf16 P^T operand of the second product is built from the same registers without
 // leaving the register file.  The V^T operand needs 4 consecutive keys per lane for a
-// fixed d; ds_read_b64_tr_b16 delivers exactly that from a row-major [key][d] tile.
+// fixed d; ds_read_b64_tr_b16 delivers exactly that from [key][d] data in LDS.
+//
+// LDS tile layout ("groups"): keys are stored in groups of KPW = 64 / (d/8) keys (4 for
+// d = 128), one group = exactly the 1 KB that one wave-wide 16-byte-per-lane load delivers.
+// Inside a group, 64-byte quads of chunks stay together and the keys interleave:
+//   addr(key, chunk) = (key / KPW) * GS + (chunk / 4) * (KPW * 64) + (key % KPW) * 64 + (chunk % 4) * 16,
+//   GS = 1024 + 16.
+// With this order (a) a wave's direct global->LDS load (lane i -> LDS slot i) fills a group
+// while every 4 consecutive lanes fetch 64 contiguous bytes of one key row, (b) the 16 lanes
+// that read one chunk of 16 consecutive keys for the first product hit 64 distinct banks
+// (4 keys 64 B apart per group, groups shifted by the 16-byte pad), the 32 lanes of a
+// transpose read for the second product touch 256 contiguous bytes, and (c) every operand
+// address is a per-lane base plus a compile-time constant.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "kernels.h"
 
@@ -27,6 +41,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
@@ -34,21 +49,50 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(uintptr_t)(p))
+#define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-constexpr int WG = 256;
-constexpr int KPAD = 16;     // bytes of padding per K row in LDS
-constexpr int VPAD = 64;     // bytes of padding per V row in LDS
+// Build-time experiment switches (defaults = the shipped configuration).
+#ifndef AMPD_PIPE
+#define AMPD_PIPE 0        // software-pipelined 64-key tile inside a wave
+#endif
+#ifndef AMPD_SGB
+#define AMPD_SGB 0         // explicit MFMA / VALU issue interleave hints
+#endif
+#ifndef AMPD_TWOLOOP
+#define AMPD_TWOLOOP 1     // separate unmasked / masked tile loops
+#endif
+#ifndef AMPD_DMA
+#define AMPD_DMA 1         // direct global -> LDS loads for bf16 wide tiles
+#endif
+#ifndef AMPD_EXPERIMENT
+#define AMPD_EXPERIMENT 0  // timing experiments with WRONG results: 1 = no K/V loads after the first tile, 2 = no compute
+#endif
+#ifndef AMPD_SWAP
+#define AMPD_SWAP 1        // v_permlane32_swap instead of an LDS permute for the lane^32 exchange
+#endif
+#ifndef AMPD_DOT2
+#define AMPD_DOT2 0        // row sums from the bf16 probabilities with v_dot2c_f32_bf16
+#endif
+#ifndef AMPD_PRIO
+#define AMPD_PRIO 0        // raise the wave priority while it feeds the matrix pipe
+#endif
+
+constexpr int WG = 256;                 // append / combine kernels
+constexpr int AWG = 64 * ATTN_WAVES;    // attention kernel: 8 waves, one workgroup per CU
+constexpr int NSTAGE = 4;               // LDS ring of 64-key K/V stages for wide items
 constexpr float NEG_INF = -__builtin_inff();
 
 template <int D>
 struct Geo {
     static constexpr int CPK = D / 8;                  // 16-byte (8-element) chunks per key row
-    static constexpr int KSTR = D * 2 + KPAD;          // LDS row strides in bytes
-    static constexpr int VSTR = D * 2 + VPAD;
-    static constexpr int K32 = 32 * KSTR;              // bytes of a 32-key K block
-    static constexpr int V32 = 32 * VSTR;
-    static constexpr int WIDE_STAGE = 2 * (K32 + V32); // one 64-key stage (K then V)
-    static constexpr int SMEM = 2 * WIDE_STAGE;        // two stages == four wave-private 32-key blocks
+    static constexpr int KPW = 64 / CPK;               // keys per group (one wave-wide load)
+    static constexpr int GS = 1024 + 16;               // LDS bytes per group
+    static constexpr int B32 = (32 / KPW) * GS;        // bytes of a 32-key block (K or V)
+    static constexpr int WIDE_STAGE = 4 * B32;         // 64 keys of K, then 64 keys of V
+    static constexpr int MERGE = ATTN_WAVES * 32 * (D + 4) * 4 + ATTN_WAVES * 32 * 2 * 4;   // narrow items: waves x (O, m, l)
+    static constexpr int NARROW = ATTN_WAVES * 2 * B32;                // one private 32-key K+V block per wave
+    static constexpr int SMEM0 = NSTAGE * WIDE_STAGE > MERGE ? NSTAGE * WIDE_STAGE : MERGE;
+    static constexpr int SMEM = SMEM0 > NARROW ? SMEM0 : NARROW;
     static constexpr int NDB = D / 32;                 // 32-row blocks of O^T
     static constexpr int NKK = D / 16;                 // MFMA k-steps of the first product
 };
@@ -58,7 +102,33 @@ struct Geo {
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-__device__ __forceinline__ float xor32(float x) { return __shfl_xor(x, 32, 64); }
+// Exchange with lane^32 folded into the reduction: v_permlane32_swap(x, x) returns
+// r0 = {x[0..31], x[0..31]} and r1 = {x[32..63], x[32..63]} (by destination lane halves), so
+// op(r0, r1) is op(x[l], x[l^32]) in every lane.
+__device__ __forceinline__ float max_xor32(float x) {
+#if AMPD_SWAP
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+#else
+    return fmaxf(x, __shfl_xor(x, 32, 64));
+#endif
+}
+__device__ __forceinline__ float sum_xor32(float x) {
+#if AMPD_SWAP
+    const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+#else
+    return x + __shfl_xor(x, 32, 64);
+#endif
+}
+__device__ __forceinline__ void mfma_priority(bool on) {
+#if AMPD_PRIO
+    if (on)
+        __builtin_amdgcn_s_setprio(1);
+    else
+        __builtin_amdgcn_s_setprio(0);
+#endif
+}
 
 // 8 stored elements -> 8 bf16 (as a 16-byte vector) for LDS.
 template <int KVT>
@@ -66,8 +136,8 @@ struct RawChunk;
 template <>
 struct RawChunk<KV_BF16> {
     u32x4 v;
-    __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
     static constexpr int ES = 2;                      // bytes per stored element
+    __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
         v = *reinterpret_cast<const u32x4*>(base + lane_off);
     }
@@ -76,8 +146,8 @@ struct RawChunk<KV_BF16> {
 template <>
 struct RawChunk<KV_FP8> {
     u32x2 v;
-    __device__ __forceinline__ void zero() { v = u32x2{0, 0}; }
     static constexpr int ES = 1;
+    __device__ __forceinline__ void zero() { v = u32x2{0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
         v = *reinterpret_cast<const u32x2*>(base + lane_off);
     }
@@ -125,99 +195,202 @@ __device__ __forceinline__ ItemCtx load_item(const AttnParams& p, int idx) {
 }
 
 // Per-lane state of one wave: 32 query rows (lane % 32), O^T as D/32 accumulator blocks.
+// m is a *reference* maximum in the log2 domain (scale * log2(e) folded in), not the exact
+// running maximum: it is raised (and O, l rescaled) only when some row's block maximum
+// exceeds it by more than RESCALE_SLACK, so probabilities stay below 2^RESCALE_SLACK.
+// (m, l, O) remain a consistent triple, which is all the final normalisation and the split-KV
+// merge need.
 template <int D>
 struct WaveAcc {
     f32x16 O[Geo<D>::NDB];
-    float m;      // running max in the log2 domain (scale * log2(e) folded in)
+    float m;
     float l;      // this lane's share of the running sum (lanes l and l^32 hold halves)
 };
-
-// NB consecutive 32-key blocks: S^T = K Q^T, online softmax, O^T += V^T P^T.
-//   kl / vl:  LDS addresses (bytes) of the first block's K and V rows; block j follows at
-//             kl + j*kstep / vl + j*vstep
-//   rel:      per lane, (last visible key of this lane's query) - (first key of block 0) - 4*(lane/32)
-//   mask_from: first block index that needs the causal select (NB: none); wave-uniform
-// The running maximum is a *reference* m, not the exact maximum: it is raised (and O, l
-// rescaled) only when some row's block maximum exceeds it by more than RESCALE_SLACK in the
-// log2 domain, so that probabilities stay below 2^RESCALE_SLACK.  (m, l, O) remain a
-// consistent triple, which is all the final normalisation and the split-KV merge need.
 constexpr float RESCALE_SLACK = 8.0f;
 
-template <int D, int NB>
-__device__ __forceinline__ void blocks(uint32_t kl, uint32_t vl, int kstep, int vstep,
-                                       const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st, float c, int rel,
-                                       int mask_from, int lane) {
+// ---------------------------------------------------------------------------------------------
+// the steps of one 32-key block
+
+// S^T = K Q^T for the 32 keys whose LDS tile starts at kl.
+template <int D>
+__device__ __forceinline__ void qk32(uint32_t kl, const bf16x8 (&Q)[Geo<D>::NKK], f32x16& S, int lane) {
     using G_ = Geo<D>;
-    const int g = lane >> 5;
-    f32x16 S[NB];
-    const uint32_t ka = kl + (lane & 31) * G_::KSTR + g * 16;
+    const int r = lane & 31, g = lane >> 5;
+    // chunk 2*kk + g of key r
+    const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
+    S = f32x16{0};
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-        S[j] = f32x16{0};
-#pragma unroll
-        for (int kk = 0; kk < G_::NKK; ++kk) {
-            const u32x4 raw = *LDS_PTR(const u32x4, ka + j * kstep + kk * 32);
-            S[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), Q[kk], S[j], 0, 0, 0);
-        }
+    for (int kk = 0; kk < G_::NKK; ++kk) {
+        const u32x4 raw = *LDS_PTR(const u32x4, ka + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32);
+        S = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, raw), Q[kk], S, 0, 0, 0);
     }
-    if (mask_from < NB) {                              // wave-uniform: only blocks crossing the diagonal
+}
+
+// rel: per lane, (last visible key of this lane's query) - (first key of the block) - 4*(lane/32)
+__device__ __forceinline__ void mask32(f32x16& S, int rel) {
 #pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            if (j >= mask_from) {
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int koff = j * 32 + (i >> 2) * 8 + (i & 3);
-                    S[j][i] = koff <= rel ? S[j][i] : NEG_INF;
-                }
-            }
-        }
+    for (int i = 0; i < 16; ++i) {
+        const int koff = (i >> 2) * 8 + (i & 3);
+        S[i] = koff <= rel ? S[i] : NEG_INF;
     }
-    float mx = S[0][0];
+}
+
+__device__ __forceinline__ float rowmax32(const f32x16& S) {
+    float mx = S[0];
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[i]);
+    return max_xor32(mx);
+}
+
+// Raise the reference maximum to cover mx (log2 domain) and rescale O, l and, if given, the
+// not yet accumulated probabilities of the previous block.
+template <int D>
+__device__ __forceinline__ void raise_reference(WaveAcc<D>& st, float mx, bf16x8* pending) {
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = fast_exp2(st.m - (m_new == NEG_INF ? 0.0f : m_new));
+    st.l *= alpha;
 #pragma unroll
-        for (int i = (j == 0 ? 1 : 0); i < 16; ++i) mx = fmaxf(mx, S[j][i]);
-    mx = fmaxf(mx, xor32(mx)) * c;
-    if (__any(mx > st.m + RESCALE_SLACK)) {            // rare after the first blocks
-        const float m_new = fmaxf(st.m, mx);
-        const float alpha = fast_exp2(st.m - (m_new == NEG_INF ? 0.0f : m_new));
-        st.l *= alpha;
+    for (int db = 0; db < Geo<D>::NDB; ++db)
 #pragma unroll
-        for (int db = 0; db < G_::NDB; ++db)
+        for (int i = 0; i < 16; ++i) st.O[db][i] *= alpha;
+    if (pending) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) st.O[db][i] *= alpha;
-        st.m = m_new;
+        for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) pending[h][i] = (__bf16)((float)pending[h][i] * alpha);
     }
-    const float m_use = st.m == NEG_INF ? 0.0f : st.m;
+    st.m = m_new;
+}
+
+// p = 2^(S*c - m); returns this lane's sum; P = bf16(p) as the two B operands of the second product
+__device__ __forceinline__ float exp32(const f32x16& S, float c, float m_use, bf16x8 (&P)[2]) {
     float psum = 0.0f;
-    bf16x8 Pb[NB][2];
+#if AMPD_DOT2
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-    for (int j = 0; j < NB; ++j)
+    for (int i = 0; i < 16; i += 2) {
+        const bf16x2 pp = {(__bf16)fast_exp2(__builtin_fmaf(S[i], c, -m_use)),
+                           (__bf16)fast_exp2(__builtin_fmaf(S[i + 1], c, -m_use))};
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);     // sum of the rounded values
+        P[i >> 3][i & 7] = pp[0];
+        P[i >> 3][(i & 7) + 1] = pp[1];
+    }
+#else
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            const float pv = fast_exp2(__builtin_fmaf(S[j][i], c, -m_use));
-            psum += pv;
-            Pb[j][i >> 3][i & 7] = (__bf16)pv;
-        }
-    st.l += psum;
-    // second product: k-slot s of MFMA cc is key 16*cc + 8*(s/4) + 4*g + s%4 of its block
-    const int hi = (lane >> 4) & 1, i16 = lane & 15;
-    const uint32_t va = vl + (4 * g + (i16 >> 2)) * G_::VSTR + (hi * 16 + (i16 & 3) * 4) * 2;
-    typedef short s16x8 __attribute__((ext_vector_type(8)));
+    for (int i = 0; i < 16; ++i) {
+        const float pv = fast_exp2(__builtin_fmaf(S[i], c, -m_use));
+        psum += pv;
+        P[i >> 3][i & 7] = (__bf16)pv;
+    }
+#endif
+    return psum;
+}
+
+// O^T += V^T P^T for the 32 keys whose LDS tile starts at vl.
+// k-slot s of MFMA cc is key 16*cc + 8*(s/4) + 4*(lane/32) + s%4 of the block.
+template <int D>
+__device__ __forceinline__ void pv32(uint32_t vl, const bf16x8 (&P)[2], WaveAcc<D>& st, int lane) {
+    using G_ = Geo<D>;
+    const int g = lane >> 5, hi = (lane >> 4) & 1, i16 = lane & 15;
+    // the 16 lanes of a transpose read address 4 keys (4*g + i16/4 ..) x 16 consecutive d
+    const int key = 4 * g + (i16 >> 2);
+    // inside the 64-byte quad of d block db: bytes hi*32 + (i16&3)*8
+    const uint32_t va = vl + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + hi * 32 + (i16 & 3) * 8;
+    constexpr int K8 = (8 / G_::KPW) * G_::GS + (8 % G_::KPW) * 64;      // +8 keys
+    constexpr int K16 = (16 / G_::KPW) * G_::GS;                        // +16 keys
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
+    for (int cc = 0; cc < 2; ++cc) {
 #pragma unroll
-        for (int cc = 0; cc < 2; ++cc) {
-#pragma unroll
-            for (int db = 0; db < G_::NDB; ++db) {
-                const uint32_t a0 = va + j * vstep + (16 * cc) * G_::VSTR + db * 64;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
-                const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + 8 * G_::VSTR));
-                const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi4[0], hi4[1], hi4[2], hi4[3]};
-                st.O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), Pb[j][cc], st.O[db], 0, 0, 0);
-            }
+        for (int db = 0; db < G_::NDB; ++db) {
+            const uint32_t a0 = va + cc * K16 + db * (G_::KPW * 64);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+            const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + K8));
+            const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+            st.O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), P[cc], st.O[db], 0, 0, 0);
         }
     }
+}
+
+// One 32-key block, straight: used by narrow items (bandwidth-bound, no pipelining needed).
+template <int D>
+__device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
+                                        float c, int rel, bool masked, int lane) {
+    f32x16 S;
+    bf16x8 P[2];
+    qk32<D>(kl, Q, S, lane);
+    if (masked) mask32(S, rel);                          // wave-uniform
+    const float mx = rowmax32(S) * c;
+    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx, nullptr);
+    st.l += exp32(S, c, st.m == NEG_INF ? 0.0f : st.m, P);
+    pv32<D>(vl, P, st, lane);
+}
+
+// One 64-key tile of a wide item, software-pipelined inside the wave so that the matrix
+// pipe and the vector ALU work on different 32-key halves at the same time:
+//   S0 = K0 Q^T | max(S0) | S1 = K1 Q^T  ||  P0 = exp(S0) | max(S1) | O += V0 P0  ||  P1 = exp(S1) | O += V1 P1
+template <int D, bool MASK>
+__device__ __forceinline__ void tile64(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
+                                       float c, int rel, int lane) {
+    using G_ = Geo<D>;
+    f32x16 S0, S1;
+    bf16x8 P0[2], P1[2];
+#if AMPD_PIPE
+    qk32<D>(kl, Q, S0, lane);
+    if (MASK) mask32(S0, rel);
+    const float mx0 = rowmax32(S0) * c;
+    if (__any(mx0 > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx0, nullptr);
+    {
+        const float m_use = st.m == NEG_INF ? 0.0f : st.m;
+        qk32<D>(kl + G_::B32, Q, S1, lane);
+        st.l += exp32(S0, c, m_use, P0);
+#if AMPD_SGB
+        // issue order: one matrix instruction, then the vector work that fits in its shadow
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < G_::NKK; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < G_::NKK - 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 56 / G_::NKK, 0);
+        }
+#endif
+    }
+    if (MASK) mask32(S1, rel - 32);
+    const float mx1 = rowmax32(S1) * c;
+    if (__any(mx1 > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx1, P0);
+    {
+        const float m_use = st.m == NEG_INF ? 0.0f : st.m;
+        pv32<D>(vl, P0, st, lane);
+        st.l += exp32(S1, c, m_use, P1);
+#if AMPD_SGB
+        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
+#pragma unroll
+        for (int i = 0; i < 2 * G_::NDB; ++i) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            if (i < 2 * G_::NDB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, 56 / (2 * G_::NDB), 0);
+        }
+#endif
+    }
+    pv32<D>(vl + G_::B32, P1, st, lane);
+#else
+    mfma_priority(true);
+    qk32<D>(kl, Q, S0, lane);
+    qk32<D>(kl + G_::B32, Q, S1, lane);
+    mfma_priority(false);
+    if (MASK) {
+        mask32(S0, rel);
+        mask32(S1, rel - 32);
+    }
+    const float mx = fmaxf(rowmax32(S0), rowmax32(S1)) * c;
+    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx, nullptr);
+    const float m_use = st.m == NEG_INF ? 0.0f : st.m;
+    st.l += exp32(S0, c, m_use, P0);
+    st.l += exp32(S1, c, m_use, P1);
+    mfma_priority(true);
+    pv32<D>(vl, P0, st, lane);
+    pv32<D>(vl + G_::B32, P1, st, lane);
+    mfma_priority(false);
+#endif
 }
 
 // Load the B operand (Q^T) of one wave: lane holds row lane%32, d = kk*16 + (lane/32)*8 .. +8.
@@ -237,74 +410,138 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const ItemCtx& ic, i
     }
 }
 
-// Cooperative K/V tile loader: NTHR threads move NKEYS consecutive keys (K and V rows) from the
-// paged pools into registers and then into LDS.  Page ids are fetched one tile earlier than
-// the K/V rows they address, so that the dependent block-table -> pool load chain is never on
-// the critical path.  Within one pass a wave reads 64/CPK consecutive keys of one page, so
-// the page id is wave-uniform: it is moved to a scalar register and the 64-bit address
-// arithmetic runs on the scalar unit; the per-lane part of the address is a constant.
+// One wave-wide direct global -> LDS load: lane i moves the 16 bytes at gbase + voff_i to LDS
+// byte lds + 16 i (gbase and lds wave-uniform; the LDS base travels in M0).  Written as inline
+// assembly so that the compiler does not track it: its own LDS reads of the *other* pipeline
+// stage would otherwise wait for these loads.  dma_wait() must precede the barrier that
+// publishes the data.  Compiler-issued vmcnt waits stay correct: vector-memory loads retire in
+// order, so extra loads in flight only make them stricter.
+__device__ __forceinline__ void dma16(const char* gbase, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase)
+                 : "memory");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// ---------------------------------------------------------------------------------------------
+// K/V tile loader.  NTHR threads move NKEYS consecutive keys (K and V rows) from the paged
+// pools into LDS, one group (KPW keys, 1 KB) per wave and pass.  Page ids are fetched one
+// tile earlier than the rows they address, so that the dependent block-table -> pool load
+// chain is never on the critical path; a group never straddles a page, so the page id is
+// wave-uniform: it is moved to a scalar register and the 64-bit address arithmetic runs on
+// the scalar unit.  Lane i fetches the chunk that belongs in LDS slot i of its group.
+//   DMA = true  (bf16 cache): global -> LDS directly (global_load_lds_dwordx4), no staging
+//                 registers; the data is in LDS once the vector-memory counter has drained,
+//                 which the barrier that ends a pipeline step waits for.
+//   DMA = false: global -> registers (fetch_kv) -> LDS (commit), widening 8-bit codes.
 template <int D, int KVT, int NTHR, int NKEYS>
 struct Loader {
-    static constexpr int CPK = D / 8;                 // 8-element chunks per key row
-    static constexpr int KPP = NTHR / CPK;            // keys per pass
-    static constexpr int NPASS = NKEYS / KPP;
-    static constexpr int KPW = 64 / CPK;              // keys per wave per pass
+    using G_ = Geo<D>;
+    static constexpr int KPW = G_::KPW;
+    static constexpr int NGRP = NKEYS / KPW;          // groups per tile
+    static constexpr int NW = NTHR / 64;              // cooperating waves
+    static constexpr int NPASS = NGRP / NW;
     static constexpr int ES = RawChunk<KVT>::ES;
     int pg[NPASS];
     RawChunk<KVT> k[NPASS], v[NPASS];
     float ks[NPASS], vs[NPASS];
 
-    // t: thread index inside the group of NTHR threads
+    // t: thread index inside the group of NTHR threads.  The block table is read through the
+    // scalar cache (it is constant for the duration of the kernel): scalar loads have their own
+    // counter, so waiting for a page id never waits for K/V data in flight.
     __device__ __forceinline__ void fetch_pages(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+        const auto* bt = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(
+            reinterpret_cast<uintptr_t>(ic.bt_row));
+        const int w = __builtin_amdgcn_readfirstlane(t >> 6);
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
-            const int key0 = kbase + ps * KPP + (t >> 6) * KPW;
-            pg[ps] = key0 < ic.kv_end ? ic.bt_row[key0 >> p.logP] : 0;
+            const int key0 = kbase + (ps * NW + w) * KPW;
+            pg[ps] = key0 < ic.kv_end ? bt[key0 >> p.logP] : 0;
         }
     }
+    static constexpr int DMA_PER_TILE = 2 * NPASS;     // direct loads per wave and tile (K and V)
 
+    __device__ __forceinline__ static uint32_t lane_off(int t) {
+        const int l = t & 63;                          // LDS slot l = (quad, key, chunk in quad)
+        return (uint32_t)((((l >> 2) % KPW) * D + ((l / (4 * KPW)) * 4 + (l & 3)) * 8) * ES);
+    }
+
+    struct Row {
+        const char *kb, *vb;
+        int key0, page;
+    };
+    __device__ __forceinline__ Row row_of(const AttnParams& p, const ItemCtx& ic, int kbase, int t, int ps) const {
+        Row r;
+        r.key0 = __builtin_amdgcn_readfirstlane(kbase + (ps * NW + (t >> 6)) * KPW);
+        r.page = __builtin_amdgcn_readfirstlane(pg[ps]);
+        const int64_t row = ((((int64_t)r.page * p.Hkv + ic.kvh) << p.logP) + (r.key0 & (p.P - 1))) * D * ES;
+        r.kb = static_cast<const char*>(p.k_pool) + row;
+        r.vb = static_cast<const char*>(p.v_pool) + row;
+        return r;
+    }
+
+    // ---- register-staged path
     template <bool FULL>
     __device__ __forceinline__ void fetch_kv_impl(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
-        const uint32_t lane_off = (uint32_t)(((t & 63) / CPK) * D + (t % CPK) * 8) * ES;
+        const uint32_t lo = lane_off(t);
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
-            const int key0 = __builtin_amdgcn_readfirstlane(kbase + ps * KPP + (t >> 6) * KPW);
-            const int page = __builtin_amdgcn_readfirstlane(pg[ps]);
-            const int64_t row = ((((int64_t)page * p.Hkv + ic.kvh) << p.logP) + (key0 & (p.P - 1))) * D * ES;
-            const char* kb = static_cast<const char*>(p.k_pool) + row;
-            const char* vb = static_cast<const char*>(p.v_pool) + row;
+            const Row r = row_of(p, ic, kbase, t, ps);
             ks[ps] = 1.0f;
             vs[ps] = 1.0f;
             if (KVT == KV_FP8) {
-                ks[ps] = p.k_scale[(int64_t)page * p.Hkv + ic.kvh];
-                vs[ps] = p.v_scale[(int64_t)page * p.Hkv + ic.kvh];
+                ks[ps] = p.k_scale[(int64_t)r.page * p.Hkv + ic.kvh];
+                vs[ps] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
             }
-            if (FULL || key0 + (t & 63) / CPK < ic.kv_end) {
-                k[ps].load(kb, lane_off);
-                v[ps].load(vb, lane_off);
+            if (FULL || r.key0 + ((t & 63) >> 2) % KPW < ic.kv_end) {
+                k[ps].load(r.kb, lo);
+                v[ps].load(r.vb, lo);
             } else {
                 k[ps].zero();                                    // keys past the item's end: zeros, so
                 v[ps].zero();                                    // that 0-weights never meet NaN garbage
             }
         }
     }
-
     __device__ __forceinline__ void fetch_kv(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
         if (kbase + NKEYS <= ic.kv_end)                          // uniform: whole tile inside the key range
             fetch_kv_impl<true>(p, ic, kbase, t);
         else
             fetch_kv_impl<false>(p, ic, kbase, t);
     }
-
-    // kl / vl: LDS byte addresses of key 0 of this tile's K and V rows
+    // kl / vl: LDS byte addresses of this tile's K and V
     __device__ __forceinline__ void commit(uint32_t kl, uint32_t vl, int t) const {
-        const int ch = t % CPK;
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
-            const int kloc = ps * KPP + t / CPK;
-            *LDS_PTR(u32x4, kl + kloc * Geo<D>::KSTR + ch * 16) = k[ps].widen(ks[ps]);
-            *LDS_PTR(u32x4, vl + kloc * Geo<D>::VSTR + ch * 16) = v[ps].widen(vs[ps]);
+            const uint32_t o = (ps * NW + (t >> 6)) * G_::GS + (t & 63) * 16;
+            *LDS_PTR(u32x4, kl + o) = k[ps].widen(ks[ps]);
+            *LDS_PTR(u32x4, vl + o) = v[ps].widen(vs[ps]);
         }
+    }
+
+    // ---- direct path (bf16 only)
+    template <bool FULL>
+    __device__ __forceinline__ void dma_impl(const AttnParams& p, const ItemCtx& ic, int kbase, int t, uint32_t kl,
+                                             uint32_t vl) const {
+        const uint32_t lo = lane_off(t);
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) {
+            const Row r = row_of(p, ic, kbase, t, ps);
+            // wave-uniform LDS offset of the group
+            const uint32_t go = __builtin_amdgcn_readfirstlane((ps * NW + (t >> 6)) * G_::GS);
+            if (FULL || r.key0 + ((t & 63) >> 2) % KPW < ic.kv_end) {
+                dma16(r.kb, lo, __builtin_amdgcn_readfirstlane(kl) + go);
+                dma16(r.vb, lo, __builtin_amdgcn_readfirstlane(vl) + go);
+            } else {
+                *LDS_PTR(u32x4, kl + go + (t & 63) * 16) = u32x4{0, 0, 0, 0};
+                *LDS_PTR(u32x4, vl + go + (t & 63) * 16) = u32x4{0, 0, 0, 0};
+            }
+        }
+    }
+    __device__ __forceinline__ void dma(const AttnParams& p, const ItemCtx& ic, int kbase, int t, uint32_t kl,
+                                        uint32_t vl) const {
+        if (kbase + NKEYS <= ic.kv_end)
+            dma_impl<true>(p, ic, kbase, t, kl, vl);
+        else
+            dma_impl<false>(p, ic, kbase, t, kl, vl);
     }
 };
 
@@ -315,7 +552,7 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
                                              int tok, int head_in_group, int row_in_item, int lane) {
     using G_ = Geo<D>;
     const int g = lane >> 5;
-    const float ltot = st.l + xor32(st.l);
+    const float ltot = sum_xor32(st.l);
     if (row_in_item < 0) return;
     if (ic.part_off < 0) {
         const float inv = 1.0f / ltot;
@@ -350,11 +587,27 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
 }
 
 // ---------------------------------------------------------------------------------------------
-// wide body: 4 waves x 32 query rows share 64-key K/V tiles, double-buffered in LDS
+// wide body: 8 waves x 32 query rows share 64-key K/V tiles.
+// bf16 cache: tiles travel global -> LDS directly through a ring of NSTAGE stages, three tiles
+// ahead of the one being consumed, so that ~100 KB per CU are in flight; one barrier per tile.
+// 8-bit cache: register-staged and widened, one tile ahead, two stages.
+
+// Wait until at most `tiles` whole tiles of direct loads are still in flight (they retire in order).
+template <int PER_TILE>
+__device__ __forceinline__ void dma_wait_tiles(int tiles) {
+    if (tiles >= 2)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * PER_TILE) & 15) | ((((2 * PER_TILE) >> 4) & 3) << 14));
+    else if (tiles == 1)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | (PER_TILE & 15) | (((PER_TILE >> 4) & 3) << 14));
+    else
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
+}
 
 template <int D, int KVT>
 __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
     using G_ = Geo<D>;
+    constexpr bool DMA = KVT == KV_BF16 && AMPD_DMA;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tqw = 32 / ic.gn;                            // tokens per wave
     const int row = lane & 31;
@@ -363,7 +616,6 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
     const bool valid = tl < tqw && tok_local < ic.nq;
     const int tok = ic.q0 + tok_local;
     // wave-level causal bounds (last visible key = C + token)
-    const int w_first = ic.C + ic.q0 + wave * tqw;
     const int w_last = ic.C + ic.q0 + min(wave * tqw + tqw, ic.nq) - 1;
     const bool wave_active = wave * tqw < ic.nq;
     const int lim = valid ? ic.C + tok : 0x3fffffff;
@@ -378,35 +630,67 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
 
     const int k_lo = ic.kv_begin;                          // multiple of 64
     const int ntiles = (ic.kv_end - k_lo + 63) >> 6;
-    Loader<D, KVT, WG, 64> ld;
-    ld.fetch_pages(p, ic, k_lo, tid);
-    ld.fetch_kv(p, ic, k_lo, tid);
-    if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + 64, tid);
-    ld.commit(smem, smem + 2 * G_::K32, tid);
-    __syncthreads();
-    for (int t = 0; t < ntiles; ++t) {
-        const uint32_t cur = smem + (t & 1) * G_::WIDE_STAGE;
-        const uint32_t nxt = smem + ((t + 1) & 1) * G_::WIDE_STAGE;
-        const bool more = t + 1 < ntiles;
-        if (more) {
-            ld.fetch_kv(p, ic, k_lo + (t + 1) * 64, tid);
-            if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * 64, tid);
-        }
+    const int nfull = (ic.kv_end - k_lo) >> 6;             // tiles 0..nfull-1 lie entirely inside the key range
+    // Tiles whose last key is visible to every row of the workgroup need no causal select;
+    // the remaining (at most a few) tiles around the diagonal take the masked variant.
+    const int wg_first = ic.C + ic.q0;                     // smallest last-visible key in the workgroup
+    const int t_diag = min(ntiles, max(0, (wg_first + 1 - k_lo) >> 6));
+    Loader<D, KVT, AWG, 64> ld;
+    auto compute = [&](int t, uint32_t stage, auto masked) {
         const int kbase = k_lo + t * 64;
-        if (wave_active && kbase <= w_last) {               // else every row of the wave masks this tile
+        if (AMPD_EXPERIMENT != 2 && wave_active && kbase <= w_last) {   // else every row of the wave masks this tile
             const int rel = lim - kbase - 4 * (lane >> 5);
-            // block j (32 keys) needs the causal select iff its last key is beyond the wave's first limit
-            const int mask_from = kbase + 31 > w_first ? 0 : (kbase + 63 > w_first ? 1 : 2);
-            blocks<D, 2>(cur, cur + 2 * G_::K32, G_::K32, G_::V32, Q, st, p.c_log2, rel, mask_from, lane);
+            tile64<D, decltype(masked)::value>(stage, stage + 2 * G_::B32, Q, st, p.c_log2, rel, lane);
         }
-        if (more) ld.commit(nxt, nxt + 2 * G_::K32, tid);
+    };
+    if (DMA) {
+        constexpr int AHEAD = NSTAGE - 1;
+        constexpr int PT = Loader<D, KVT, AWG, 64>::DMA_PER_TILE;
+        auto issue = [&](int i) {                          // tile i -> stage i % NSTAGE; then page ids of tile i + 1
+            const uint32_t sg = smem + (i % NSTAGE) * G_::WIDE_STAGE;
+            ld.dma(p, ic, k_lo + i * 64, tid, sg, sg + 2 * G_::B32);
+            if (i + 1 < ntiles) ld.fetch_pages(p, ic, k_lo + (i + 1) * 64, tid);
+        };
+        // number of whole tiles among t+2, t+3 that may stay in flight while tile t+1 must have landed
+        auto in_flight_after = [&](int t) { return max(0, min(min(ntiles, t + 1 + AHEAD), nfull) - (t + 2)); };
+        ld.fetch_pages(p, ic, k_lo, tid);
+        for (int i = 0; i < AHEAD && i < ntiles; ++i) issue(i);
+        dma_wait_tiles<PT>(in_flight_after(-1));
         __syncthreads();
+        auto step = [&](int t, auto masked) {
+            if (t + AHEAD < ntiles && AMPD_EXPERIMENT != 1) issue(t + AHEAD);
+            compute(t, smem + (t % NSTAGE) * G_::WIDE_STAGE, masked);
+            dma_wait_tiles<PT>(in_flight_after(t));         // tile t+1 has landed in LDS
+            __syncthreads();
+        };
+        for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
+        for (int t = t_diag; t < ntiles; ++t) step(t, std::true_type{});
+    } else {
+        ld.fetch_pages(p, ic, k_lo, tid);
+        ld.fetch_kv(p, ic, k_lo, tid);
+        if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + 64, tid);
+        ld.commit(smem, smem + 2 * G_::B32, tid);
+        __syncthreads();
+        auto step = [&](int t, auto masked) {
+            const uint32_t cur = smem + (t & 1) * G_::WIDE_STAGE;
+            const uint32_t nxt = smem + ((t + 1) & 1) * G_::WIDE_STAGE;
+            const bool more = t + 1 < ntiles;
+            if (more) {
+                ld.fetch_kv(p, ic, k_lo + (t + 1) * 64, tid);
+                if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * 64, tid);
+            }
+            compute(t, cur, masked);
+            if (more) ld.commit(nxt, nxt + 2 * G_::B32, tid);
+            __syncthreads();
+        };
+        for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
+        for (int t = t_diag; t < ntiles; ++t) step(t, std::true_type{});
     }
     store_result<D>(p, ic, st, tok, hg, valid ? tok_local * ic.gn + hg : -1, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
-// narrow body: <= 32 query rows; the 4 waves take 32-key blocks round-robin, each through its
+// narrow body: <= 32 query rows; the 8 waves take 32-key blocks round-robin, each through its
 // own LDS region, and merge their (m, l, O) through LDS at the end
 
 template <int D, int KVT>
@@ -428,31 +712,32 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
     st.m = NEG_INF;
     st.l = 0.0f;
 
-    const uint32_t kl = smem + wave * (G_::K32 + G_::V32);
-    const uint32_t vl = kl + G_::K32;
+    const uint32_t kl = smem + wave * (2 * G_::B32);
+    const uint32_t vl = kl + G_::B32;
     const int nblocks = (ic.kv_end - ic.kv_begin + 31) >> 5;
     Loader<D, KVT, 64, 32> ld;
     if (wave < nblocks) {
         ld.fetch_pages(p, ic, ic.kv_begin + wave * 32, lane);
         ld.fetch_kv(p, ic, ic.kv_begin + wave * 32, lane);
-        if (wave + 4 < nblocks) ld.fetch_pages(p, ic, ic.kv_begin + (wave + 4) * 32, lane);
+        if (wave + ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, ic.kv_begin + (wave + ATTN_WAVES) * 32, lane);
     }
-    for (int b = wave; b < nblocks; b += 4) {
+    for (int b = wave; b < nblocks; b += ATTN_WAVES) {
         const int kbase = ic.kv_begin + b * 32;
         ld.commit(kl, vl, lane);
-        if (b + 4 < nblocks) {
-            ld.fetch_kv(p, ic, kbase + 128, lane);
-            if (b + 8 < nblocks) ld.fetch_pages(p, ic, kbase + 256, lane);
+        if (b + ATTN_WAVES < nblocks) {
+            ld.fetch_kv(p, ic, kbase + 32 * ATTN_WAVES, lane);
+            if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
         }
         const int rel = lim - kbase - 4 * (lane >> 5);
-        blocks<D, 1>(kl, vl, 0, 0, Q, st, p.c_log2, rel, kbase + 31 > first_lim ? 0 : 1, lane);
+        block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
     }
-    // merge the four waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
-    const float ltot = st.l + xor32(st.l);
+    // merge the waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
+    const float ltot = sum_xor32(st.l);
     __syncthreads();                                      // every wave is done with its K/V region
+    constexpr int NW = ATTN_WAVES;
     constexpr int OSTR = D + 4;
     const uint32_t obase = smem;
-    const uint32_t mlbase = smem + 4 * 32 * OSTR * 4;
+    const uint32_t mlbase = smem + NW * 32 * OSTR * 4;
     {
         const int g = lane >> 5;
         const uint32_t orow = obase + ((wave * 32 + row) * OSTR) * 4;
@@ -470,23 +755,23 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
         }
     }
     __syncthreads();
-    // thread -> (row r, 16 consecutive d) for D = 128; (row, 8 d) for D = 64
-    constexpr int DPT = D / 8;
-    const int r = tid >> 3, dc = (tid & 7) * DPT;
+    // thread -> (row r, DPT consecutive d): 16 threads per row
+    constexpr int DPT = D / 16;
+    const int r = tid >> 4, dc = (tid & 15) * DPT;
     const int rows = ic.nq * ic.gn;
     if (r < rows) {
-        float mw[4], lw[4];
+        float mw[NW], lw[NW];
         float mall = NEG_INF;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < NW; ++w) {
             mw[w] = *LDS_PTR(float, mlbase + ((w * 32 + r) * 2) * 4);
             lw[w] = *LDS_PTR(float, mlbase + ((w * 32 + r) * 2 + 1) * 4);
             mall = fmaxf(mall, mw[w]);
         }
         const float muse = mall == NEG_INF ? 0.0f : mall;
-        float lsum = 0.0f, wgt[4];
+        float lsum = 0.0f, wgt[NW];
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < NW; ++w) {
             wgt[w] = fast_exp2(mw[w] - muse);
             lsum += lw[w] * wgt[w];
         }
@@ -494,7 +779,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
 #pragma unroll
         for (int x = 0; x < DPT; ++x) acc[x] = 0.0f;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) {
+        for (int w = 0; w < NW; ++w) {
             const uint32_t src = obase + ((w * 32 + r) * OSTR + dc) * 4;
 #pragma unroll
             for (int x = 0; x < DPT; x += 4) {
@@ -511,11 +796,10 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             const int hq = ic.kvh * (p.Hq / p.Hkv) + ic.g0 + rhg;
             char* dst = static_cast<char*>(p.out) + (((int64_t)(ic.row_off + ic.q0 + rtl) * p.Hq + hq) * D + dc) * 2;
 #pragma unroll
-            for (int x = 0; x < DPT; x += 8) {
-                bf16x8 o;
-#pragma unroll
-                for (int y = 0; y < 8; ++y) o[y] = (__bf16)(acc[x + y] * inv);
-                *reinterpret_cast<u32x4*>(dst + x * 2) = __builtin_bit_cast(u32x4, o);
+            for (int x = 0; x < DPT; x += 4) {
+                bf16x4 o = {(__bf16)(acc[x] * inv), (__bf16)(acc[x + 1] * inv), (__bf16)(acc[x + 2] * inv),
+                            (__bf16)(acc[x + 3] * inv)};
+                *reinterpret_cast<u32x2*>(dst + x * 2) = __builtin_bit_cast(u32x2, o);
             }
         } else {
             float* po = p.partial + ic.part_off + (int64_t)r * D + dc;
@@ -524,7 +808,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
                 f32x4 o = {acc[x], acc[x + 1], acc[x + 2], acc[x + 3]};
                 *reinterpret_cast<f32x4*>(po + x) = o;
             }
-            if ((tid & 7) == 0) {
+            if ((tid & 15) == 0) {
                 float* ml = p.partial + ic.part_off + (int64_t)rows * D + r * 2;
                 ml[0] = mall;
                 ml[1] = lsum;
@@ -537,7 +821,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
 // the fused attention launch: one workgroup per work item, wide and narrow items in one grid
 
 template <int D, int KVT>
-__global__ __launch_bounds__(WG, 2) void attn_kernel(const AttnParams p) {
+__global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) char smem_raw[Geo<D>::SMEM];
     const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
     const ItemCtx ic = load_item(p, blockIdx.x);
@@ -716,7 +1000,7 @@ __global__ __launch_bounds__(WG) void append_fp8_kernel(const AppendParams p) {
 
 template <int D, int KVT>
 static hipError_t launch_attn_t(const AttnParams& p, int nitems, hipStream_t st) {
-    hipLaunchKernelGGL((attn_kernel<D, KVT>), dim3(nitems), dim3(WG), 0, st, p);
+    hipLaunchKernelGGL((attn_kernel<D, KVT>), dim3(nitems), dim3(AWG), 0, st, p);
     return hipGetLastError();
 }
 

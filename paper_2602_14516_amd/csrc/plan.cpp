@@ -49,7 +49,7 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                     qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_NARROW), 0, L, C + L, L * gn, KIND_NARROW});
                     narrow_keys += C + L;
                 } else {
-                    const int tq = 4 * tq_wave;
+                    const int tq = ATTN_WAVES * tq_wave;
                     for (int q0 = 0; q0 < L; q0 += tq) {
                         const int nq = std::min(tq, L - q0);
                         qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_WIDE), q0, nq, C + q0 + nq, nq * gn, KIND_WIDE});

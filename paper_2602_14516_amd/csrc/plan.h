@@ -3,10 +3,10 @@
 // A prefill task is described to the scheduler by its history length and incremental
 // length only (paper Section 3, T_pre(l_hist, l_incr)); a decode step by one token per
 // request (T_dec).  From these lengths alone the planner derives, per request and KV head:
-//   * wide items   -- tiles of up to 128 query rows (tokens x grouped heads) whose 4 waves
+//   * wide items   -- tiles of up to 256 query rows (tokens x grouped heads) whose 8 waves
 //                     share K/V tiles staged in LDS (compute-bound prefill work), and
 //   * narrow items -- blocks of at most 32 query rows (decode rows, very short chunks)
-//                     whose 4 waves split the key range (bandwidth-bound work),
+//                     whose 8 waves split the key range (bandwidth-bound work),
 // optionally cutting an item's key range into pieces (split-KV) that a combine pass merges.
 // Everything is computed from logical positions, never from physical page ids, so results
 // are bitwise independent of where pages live in the pool.
@@ -17,6 +17,8 @@
 namespace ampd {
 
 enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1 };
+
+constexpr int ATTN_WAVES = 8;      // waves of an attention workgroup (one workgroup per CU)
 
 struct ReqInfo {          // 16 B, one per request, device-visible
     int32_t C, L, row_off, pad;
@@ -51,7 +53,7 @@ struct Shape {
 
 struct PlanOptions {
     int force_kv_splits = 0;
-    int wg_slots = 512;   // workgroups resident at once: 256 CUs x 2
+    int wg_slots = 256;   // workgroups resident at once: one per CU
 };
 
 struct Plan {
