@@ -79,8 +79,8 @@ ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_pl
 }
 
 // ---- pinned staging ring ---------------------------------------------------------------------
-// The work list is built on the host and copied to the caller's workspace with an
-// asynchronous copy from pinned memory.  Each call takes the next ring slot; a slot is reused
+// The work list is built on the host in pinned memory and copied to the caller's workspace by
+// a small upload kernel that reads the pinned buffer directly.  Each call takes the next ring slot; a slot is reused
 // only after the event recorded behind its copy has completed.
 
 struct Slot {
@@ -194,7 +194,7 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
         std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
         std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(Item));
         if (!plan.combs.empty()) std::memcpy(h + plan.off_combs, plan.combs.data(), plan.combs.size() * sizeof(CombItem));
-        HIP_TRY(hipMemcpyAsync(workspace, h, (size_t)plan.plan_bytes, hipMemcpyHostToDevice, st));
+        HIP_TRY(launch_upload(h, workspace, (size_t)plan.plan_bytes, st));
         HIP_TRY(hipEventRecord(s->ev, st));
         s->pending = true;
     }

@@ -39,6 +39,8 @@ struct AppendParams {
     int32_t C[APPEND_MAX_REQS], L[APPEND_MAX_REQS], row_off[APPEND_MAX_REQS];
 };
 
+// h_src: pinned, device-visible host memory; bytes is rounded up to 16
+hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream_t st);
 hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st);
 hipError_t launch_combine(const AttnParams& p, int D, int ncombs, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);

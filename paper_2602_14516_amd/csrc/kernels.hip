@@ -79,7 +79,14 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int WG = 256;                 // append / combine kernels
 constexpr int AWG = 64 * ATTN_WAVES;    // attention kernel: 8 waves, one workgroup per CU
-constexpr int NSTAGE = 4;               // LDS ring of 64-key K/V stages for wide items
+#ifndef AMPD_KT
+#define AMPD_KT 128
+#endif
+#ifndef AMPD_NSTAGE
+#define AMPD_NSTAGE 2
+#endif
+constexpr int KT = AMPD_KT;             // keys per LDS stage of a wide item (one barrier per stage)
+constexpr int NSTAGE = AMPD_NSTAGE;     // LDS ring of K/V stages for wide items
 constexpr float NEG_INF = -__builtin_inff();
 
 template <int D>
@@ -88,7 +95,8 @@ struct Geo {
     static constexpr int KPW = 64 / CPK;               // keys per group (one wave-wide load)
     static constexpr int GS = 1024 + 16;               // LDS bytes per group
     static constexpr int B32 = (32 / KPW) * GS;        // bytes of a 32-key block (K or V)
-    static constexpr int WIDE_STAGE = 4 * B32;         // 64 keys of K, then 64 keys of V
+    static constexpr int KTILE = (KT / 32) * B32;      // bytes of KT keys (K or V)
+    static constexpr int WIDE_STAGE = 2 * KTILE;       // KT keys of K, then KT keys of V
     static constexpr int MERGE = ATTN_WAVES * 32 * (D + 4) * 4 + ATTN_WAVES * 32 * 2 * 4;   // narrow items: waves x (O, m, l)
     static constexpr int NARROW = ATTN_WAVES * 2 * B32;                // one private 32-key K+V block per wave
     static constexpr int SMEM0 = NSTAGE * WIDE_STAGE > MERGE ? NSTAGE * WIDE_STAGE : MERGE;
@@ -595,7 +603,9 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
 // Wait until at most `tiles` whole tiles of direct loads are still in flight (they retire in order).
 template <int PER_TILE>
 __device__ __forceinline__ void dma_wait_tiles(int tiles) {
-    if (tiles >= 2)
+    if (tiles >= 3)
+        __builtin_amdgcn_s_waitcnt(0x0F70 | ((3 * PER_TILE) & 15) | ((((3 * PER_TILE) >> 4) & 3) << 14));
+    else if (tiles == 2)
         __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * PER_TILE) & 15) | ((((2 * PER_TILE) >> 4) & 3) << 14));
     else if (tiles == 1)
         __builtin_amdgcn_s_waitcnt(0x0F70 | (PER_TILE & 15) | (((PER_TILE >> 4) & 3) << 14));
@@ -629,29 +639,35 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
     st.l = 0.0f;
 
     const int k_lo = ic.kv_begin;                          // multiple of 64
-    const int ntiles = (ic.kv_end - k_lo + 63) >> 6;
-    const int nfull = (ic.kv_end - k_lo) >> 6;             // tiles 0..nfull-1 lie entirely inside the key range
+    const int ntiles = (ic.kv_end - k_lo + KT - 1) / KT;
+    const int nfull = (ic.kv_end - k_lo) / KT;             // tiles 0..nfull-1 lie entirely inside the key range
     // Tiles whose last key is visible to every row of the workgroup need no causal select;
     // the remaining (at most a few) tiles around the diagonal take the masked variant.
     const int wg_first = ic.C + ic.q0;                     // smallest last-visible key in the workgroup
-    const int t_diag = min(ntiles, max(0, (wg_first + 1 - k_lo) >> 6));
-    Loader<D, KVT, AWG, 64> ld;
+    const int t_diag = min(ntiles, max(0, (wg_first + 1 - k_lo) / KT));
+    Loader<D, KVT, AWG, KT> ld;
     auto compute = [&](int t, uint32_t stage, auto masked) {
-        const int kbase = k_lo + t * 64;
-        if (AMPD_EXPERIMENT != 2 && wave_active && kbase <= w_last) {   // else every row of the wave masks this tile
-            const int rel = lim - kbase - 4 * (lane >> 5);
-            tile64<D, decltype(masked)::value>(stage, stage + 2 * G_::B32, Q, st, p.c_log2, rel, lane);
+#pragma unroll
+        for (int h = 0; h < KT / 64; ++h) {
+            const int kbase = k_lo + t * KT + h * 64;
+            // skip 64-key halves that lie beyond the key range or that every row of the wave masks
+            if (AMPD_EXPERIMENT != 2 && wave_active && kbase <= w_last && kbase < ic.kv_end) {
+                const int rel = lim - kbase - 4 * (lane >> 5);
+                tile64<D, decltype(masked)::value>(stage + h * 2 * G_::B32, stage + G_::KTILE + h * 2 * G_::B32, Q, st,
+                                                   p.c_log2, rel, lane);
+            }
         }
     };
     if (DMA) {
         constexpr int AHEAD = NSTAGE - 1;
-        constexpr int PT = Loader<D, KVT, AWG, 64>::DMA_PER_TILE;
+        constexpr int PT = Loader<D, KVT, AWG, KT>::DMA_PER_TILE;
+        static_assert(AHEAD >= 1 && AHEAD <= 3 && 2 * PT < 64, "vmcnt budget");
         auto issue = [&](int i) {                          // tile i -> stage i % NSTAGE; then page ids of tile i + 1
             const uint32_t sg = smem + (i % NSTAGE) * G_::WIDE_STAGE;
-            ld.dma(p, ic, k_lo + i * 64, tid, sg, sg + 2 * G_::B32);
-            if (i + 1 < ntiles) ld.fetch_pages(p, ic, k_lo + (i + 1) * 64, tid);
+            ld.dma(p, ic, k_lo + i * KT, tid, sg, sg + G_::KTILE);
+            if (i + 1 < ntiles) ld.fetch_pages(p, ic, k_lo + (i + 1) * KT, tid);
         };
-        // number of whole tiles among t+2, t+3 that may stay in flight while tile t+1 must have landed
+        // whole tiles beyond t+1 that may stay in flight while tile t+1 must have landed
         auto in_flight_after = [&](int t) { return max(0, min(min(ntiles, t + 1 + AHEAD), nfull) - (t + 2)); };
         ld.fetch_pages(p, ic, k_lo, tid);
         for (int i = 0; i < AHEAD && i < ntiles; ++i) issue(i);
@@ -666,21 +682,22 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
         for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
         for (int t = t_diag; t < ntiles; ++t) step(t, std::true_type{});
     } else {
+        static_assert(NSTAGE >= 2, "two stages for the register-staged path");
         ld.fetch_pages(p, ic, k_lo, tid);
         ld.fetch_kv(p, ic, k_lo, tid);
-        if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + 64, tid);
-        ld.commit(smem, smem + 2 * G_::B32, tid);
+        if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + KT, tid);
+        ld.commit(smem, smem + G_::KTILE, tid);
         __syncthreads();
         auto step = [&](int t, auto masked) {
             const uint32_t cur = smem + (t & 1) * G_::WIDE_STAGE;
             const uint32_t nxt = smem + ((t + 1) & 1) * G_::WIDE_STAGE;
             const bool more = t + 1 < ntiles;
             if (more) {
-                ld.fetch_kv(p, ic, k_lo + (t + 1) * 64, tid);
-                if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * 64, tid);
+                ld.fetch_kv(p, ic, k_lo + (t + 1) * KT, tid);
+                if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * KT, tid);
             }
             compute(t, cur, masked);
-            if (more) ld.commit(nxt, nxt + 2 * G_::B32, tid);
+            if (more) ld.commit(nxt, nxt + G_::KTILE, tid);
             __syncthreads();
         };
         for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
@@ -995,8 +1012,23 @@ __global__ __launch_bounds__(WG) void append_fp8_kernel(const AppendParams p) {
     }
 }
 
+// Work-list upload: the workgroups read the host-built plan straight out of pinned host memory
+// and write it to the workspace (cheaper than a runtime copy command for ~100 KB).
+__global__ __launch_bounds__(WG) void upload_kernel(const u32x4* __restrict__ src, u32x4* __restrict__ dst, int n16) {
+    const int i = blockIdx.x * WG + threadIdx.x;
+    if (i < n16) dst[i] = src[i];
+}
+
 // ---------------------------------------------------------------------------------------------
 // launchers
+
+hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream_t st) {
+    const int n16 = (int)((bytes + 15) / 16);
+    if (n16 <= 0) return hipSuccess;
+    hipLaunchKernelGGL(upload_kernel, dim3((n16 + WG - 1) / WG), dim3(WG), 0, st,
+                       static_cast<const u32x4*>(h_src), static_cast<u32x4*>(d_dst), n16);
+    return hipGetLastError();
+}
 
 template <int D, int KVT>
 static hipError_t launch_attn_t(const AttnParams& p, int nitems, hipStream_t st) {
