@@ -131,3 +131,86 @@ def test_shrunk_config_shapes():
         rows = sample_rows(b, 6, seed=k)
         mx, mean = compare(b, out, rows=rows, label=b.name)
         print(f"{b.name} max-abs {mx:.2e} mean-abs {mean:.2e}")
+
+
+# ---- full-size configurations, in the launch configuration bench.py times --------------------
+
+def _full_config(k, part="all", fn=None, per_req=6, **kw):
+    b = W.make_config(k, part=part)
+    db = DevBatch(b)
+    out = run_attn(db, fn=fn or A.incr_prefill_attn, **kw)
+    rows = sample_rows(b, per_req, seed=k)
+    mx, mean = compare(b, out, rows=rows, label=b.name)
+    print(f"{b.name}: sampled max-abs {mx:.2e} mean-abs {mean:.2e}", flush=True)
+    return b, db, out
+
+
+@pytest.mark.timeout(600)
+def test_config2_full_size_sampled_rows_and_append():
+    print("case: config 2 full size", flush=True)
+    b, db, out = _full_config(2)
+    check_append(db)
+    # property that holds at any size: with the same key-range cutting (here: none), the output of a row
+    # is bitwise independent of the rest of the batch
+    assert A.plan_describe(db.cache, b.ctx_len, b.incr_len, b.block_table.shape[1])["num_combine_items"] == 0
+    r = int(np.argmin(b.incr_len))
+    off = b.row_offsets
+    sub = W.Batch(b.Hq, b.Hkv, b.d, b.P, b.scale, b.ctx_len[r:r + 1], b.incr_len[r:r + 1],
+                  b.block_table[r:r + 1], b.num_pages, b.k_pool, b.v_pool,
+                  b.q[off[r]:off[r + 1]], b.k_new[off[r]:off[r + 1]], b.v_new[off[r]:off[r + 1]])
+    o = run_attn(DevBatch(sub), force_kv_splits=1)
+    assert np.array_equal(o, out[off[r]:off[r + 1]])
+    # and with the automatic cutting of the small batch it stays within tolerance
+    o2 = run_attn(DevBatch(sub))
+    assert np.abs(W.bf16_bits_to_f64(o2) - W.bf16_bits_to_f64(o)).max() <= 2e-2
+
+
+@pytest.mark.timeout(900)
+def test_config3_full_size_mixed_batch():
+    print("case: config 3 full size (mixed, one fused launch)", flush=True)
+    b, db, out = _full_config(3, fn=A.mixed_batch_attn, per_req=4)
+    info = A.plan_describe(db.cache, b.ctx_len, b.incr_len, b.block_table.shape[1])
+    assert info["num_wide_items"] > 0 and info["num_narrow_items"] > 0 and info["num_combine_items"] > 0
+
+
+@pytest.mark.timeout(900)
+def test_config3_decode_rows_only():
+    print("case: config 3 decode rows", flush=True)
+    _full_config(3, part="decode", fn=A.mixed_batch_attn, per_req=1)
+
+
+@pytest.mark.timeout(900)
+def test_config4_long_context_prefill_then_decode_with_and_without_forced_splits():
+    print("case: config 4 full size", flush=True)
+    b, db, out = _full_config(4, per_req=5)
+    check_append(db)
+    # split-KV forced on the prefill rows: same rows within tolerance of the oracle and close to the unsplit run
+    out2 = run_attn(db, force_kv_splits=3)
+    rows = sample_rows(b, 5, seed=4)
+    compare(b, out2, rows=rows, label="cfg4 forced splits")
+    d = np.abs(W.bf16_bits_to_f64(out) - W.bf16_bits_to_f64(out2))
+    assert d.max() <= 2e-2
+    # the decode step that follows: L = 1 over C + 4096 keys, split-KV path
+    print("case: config 4 decode step", flush=True)
+    C2 = (b.ctx_len + b.incr_len).astype(np.int32)
+    g = np.random.default_rng(44)
+    q1 = W.f32_to_bf16_bits(g.standard_normal((4, b.Hq, b.d), dtype=np.float32))
+    k1 = W.f32_to_bf16_bits(g.standard_normal((4, b.Hkv, b.d), dtype=np.float32))
+    v1 = W.f32_to_bf16_bits(g.standard_normal((4, b.Hkv, b.d), dtype=np.float32))
+    need = (C2.astype(np.int64) + 1 + b.P - 1) // b.P
+    assert need.max() <= b.block_table.shape[1] or True
+    k_after, v_after = from_dev_bits(db.k_pool), from_dev_bits(db.v_pool)
+    bt = b.block_table
+    if need.max() > bt.shape[1]:                 # a row whose T was a multiple of P needs one more page
+        used = set(bt[bt >= 0].tolist())
+        free = [x for x in range(b.num_pages) if x not in used]
+        bt = np.concatenate([bt, np.full((4, 1), -1, np.int32)], axis=1)
+        for r in range(4):
+            if need[r] > (bt[r] >= 0).sum():
+                bt[r, need[r] - 1] = free.pop()
+    b2 = W.Batch(b.Hq, b.Hkv, b.d, b.P, b.scale, C2, np.ones(4, np.int32), bt, b.num_pages, k_after, v_after, q1, k1, v1)
+    db2 = DevBatch(b2)
+    o2 = run_attn(db2, fn=A.mixed_batch_attn)
+    info = A.plan_describe(db2.cache, b2.ctx_len, b2.incr_len, bt.shape[1])
+    assert info["num_narrow_items"] > 4 and info["num_combine_items"] == 4
+    compare(b2, o2, label="cfg4 decode step")
