@@ -496,7 +496,7 @@ struct Loader {
             const Row r = row_of(p, ic, kbase, t, ps);
             ks[ps] = 1.0f;
             vs[ps] = 1.0f;
-            if (KVT == KV_FP8) {
+            if (KVT == KV_FP8 && (FULL || r.key0 < ic.kv_end)) {   // (a group past the key range has no page)
                 ks[ps] = p.k_scale[(int64_t)r.page * p.Hkv + ic.kvh];
                 vs[ps] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
             }
