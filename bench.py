@@ -107,42 +107,31 @@ def make_runner(torch, A, db, fn):
     return lambda: f(db["cache"], db["C"], db["L"], db["bt"], db["q"], db["k_new"], db["v_new"], out=db["out"], workspace=ws)
 
 
-def cpu_baseline(W, batch, budget_s=20.0):
-    """Time the fp64 oracle on a bounded sample of query rows of the same batch."""
+def cpu_baseline(W, batch, budget_s=15.0):
+    """Time the fp64 oracle, as it stands, on a bounded sample of query rows of the same batch:
+    rounds of 16 random (request, query position) pairs until about budget_s seconds have passed."""
     import oracle
     cores = oracle.oracle_threads()
-    # choose rows spread over requests until the predicted cost reaches the budget
     g = np.random.default_rng(0)
-    rate_guess = 0.6e9 * cores                       # causal-pair flops/s, refined by a probe below
-    rows, fl = {}, 0
-
-    def row_flops(r, i):
-        return 4 * batch.d * batch.Hq * (int(batch.ctx_len[r]) + i + 1)
-
-    probe = {0: np.array([int(batch.incr_len[0]) - 1], np.int32)}
+    fl, n, reqs = 0, 0, set()
     t0 = time.perf_counter()
-    oracle.attn_oracle(batch.k_pool, batch.v_pool, batch.block_table, batch.ctx_len, batch.incr_len,
-                       batch.q, batch.k_new, batch.v_new, batch.P, batch.scale, rows=probe)
-    tp = time.perf_counter() - t0
-    # the probe includes the gather of one request; use it only as an upper bound on the rate
-    rate_guess = max(rate_guess, row_flops(0, int(probe[0][0])) / max(tp, 1e-3) * 0.5)
-    target = rate_guess * budget_s
-    order = [(r, i) for r in range(batch.num_reqs) for i in g.choice(int(batch.incr_len[r]), size=min(8, int(batch.incr_len[r])), replace=False)]
-    g.shuffle(order)
-    for r, i in order:
-        if fl >= target:
-            break
-        rows.setdefault(r, []).append(int(i))
-        fl += row_flops(r, int(i))
-    rows = {r: np.array(sorted(v), np.int32) for r, v in rows.items()}
-    t0 = time.perf_counter()
-    oracle.attn_oracle(batch.k_pool, batch.v_pool, batch.block_table, batch.ctx_len, batch.incr_len,
-                       batch.q, batch.k_new, batch.v_new, batch.P, batch.scale, rows=rows)
+    while time.perf_counter() - t0 < budget_s:
+        rows = {}
+        for _ in range(16):
+            r = int(g.integers(batch.num_reqs))
+            i = int(g.integers(int(batch.incr_len[r])))
+            rows.setdefault(r, set()).add(i)
+        rows = {r: np.array(sorted(v), np.int32) for r, v in rows.items()}
+        oracle.attn_oracle(batch.k_pool, batch.v_pool, batch.block_table, batch.ctx_len, batch.incr_len,
+                           batch.q, batch.k_new, batch.v_new, batch.P, batch.scale, rows=rows)
+        for r, v in rows.items():
+            reqs.add(r)
+            n += len(v)
+            fl += int(sum(4 * batch.d * batch.Hq * (int(batch.ctx_len[r]) + int(i) + 1) for i in v))
     dt = time.perf_counter() - t0
-    n = sum(len(v) for v in rows.values())
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": cores, "kind": "oracle",
-            "sample": f"{n} query positions x {batch.Hq} heads over {len(rows)} requests of the same batch "
-                      f"({fl / 1e9:.1f} GFLOP, {dt:.1f} s incl. fp64 gather of their K/V)"}
+            "sample": f"{n} random query positions x {batch.Hq} heads over {len(reqs)} requests of the same batch "
+                      f"({fl / 1e9:.1f} GFLOP of causal pairs in {dt:.1f} s, incl. the fp64 gather of their K/V)"}
 
 
 def main():
@@ -152,7 +141,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' steps, no JSON extras")
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' steps, or "
+                    "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
@@ -165,6 +155,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.only == "copycal":
+        x = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        y = torch.empty_like(x)
+        for _ in range(3):
+            y.copy_(x)
+        torch.cuda.synchronize()
+        print(json.dumps({"only": "copycal", "bytes_read": x.numel() * 4, "bytes_written": x.numel() * 4}))
+        return
 
     # ---- configuration 2: the step that is timed --------------------------------------------
     sh2 = W.CONFIG_SHAPES[2]
@@ -207,11 +206,11 @@ def main():
 
     # ---- configuration 3: decode-dominated and mixed batches (second half of the metric) ----
     mixed = None
-    if not args.no_mixed and args.only in ("", "decode", "mixed"):
+    if not args.no_mixed and args.only in ("", "decode", "mixed", "prefill3"):
         sh3 = W.CONFIG_SHAPES[3]
         mixed = {}
-        for part in (("decode", "mixed") if not args.only else (args.only,)):
-            C, L = W.config_lengths(3, part="decode" if part == "decode" else "all")
+        for part in (("decode", "prefill3", "mixed") if not args.only else (args.only,)):
+            C, L = W.config_lengths(3, part={"decode": "decode", "prefill3": "prefill", "mixed": "all"}[part])
             d3 = device_batch(torch, A, W, C, L, sh3, seed=W.BASE_SEED + 3)
             fn = make_runner(torch, A, d3, "mixed")
             ms3 = time_calls(torch, fn, 20, 3)
@@ -230,6 +229,7 @@ def main():
         if args.only:
             print(json.dumps({"only": args.only, **mixed}))
             return
+        mixed["fused_vs_separate"] = (mixed["decode"]["ms_per_step"] + mixed["prefill3"]["ms_per_step"]) / mixed["mixed"]["ms_per_step"]
 
     cpu = None
     if not args.no_cpu_baseline:

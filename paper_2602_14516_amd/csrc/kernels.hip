@@ -67,6 +67,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #ifndef AMPD_EXPERIMENT
 #define AMPD_EXPERIMENT 0  // timing experiments with WRONG results: 1 = no K/V loads after the first tile, 2 = no compute
 #endif
+#ifndef AMPD_NT
+#define AMPD_NT 1          // non-temporal K/V loads on the register-staged (narrow item) path
+#endif
 #ifndef AMPD_SWAP
 #define AMPD_SWAP 1        // v_permlane32_swap instead of an LDS permute for the lane^32 exchange
 #endif
@@ -147,7 +150,11 @@ struct RawChunk<KV_BF16> {
     static constexpr int ES = 2;                      // bytes per stored element
     __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
+#if AMPD_NT
+        v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + lane_off));   // streamed once: do not displace L2 lines
+#else
         v = *reinterpret_cast<const u32x4*>(base + lane_off);
+#endif
     }
     __device__ __forceinline__ u32x4 widen(float) const { return v; }
 };
@@ -746,7 +753,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
         }
         const int rel = lim - kbase - 4 * (lane >> 5);
-        block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
+        if (AMPD_EXPERIMENT != 2) block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
     }
     // merge the waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
     const float ltot = sum_xor32(st.l);

@@ -111,10 +111,35 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
         }
     }
 
-    // 4. longest first (stable, so the order is a function of the lengths only)
+    // 4. launch order: longest first within each kind (stable, so the order is a function of the
+    //    lengths only).  In a mixed batch the two kinds are interleaved in proportion to their
+    //    total cost, so that at any time some CUs run compute-bound tiles while others stream
+    //    decode rows, instead of one phase after the other.
     std::stable_sort(order.begin(), order.end(), [](const Cost& a, const Cost& b) { return a.cost > b.cost; });
-    std::vector<Item> sorted(out.items.size());
-    for (size_t i = 0; i < order.size(); ++i) sorted[i] = out.items[order[i].idx];
+    std::vector<int32_t> wide_ix, narrow_ix;
+    double wide_cost = 0, narrow_cost = 0;
+    for (const Cost& c : order) {
+        const bool is_wide = ((out.items[c.idx].heads >> 24) & 0xff) == KIND_WIDE;
+        (is_wide ? wide_ix : narrow_ix).push_back(c.idx);
+        (is_wide ? wide_cost : narrow_cost) += (double)c.cost;
+    }
+    std::vector<Item> sorted;
+    sorted.reserve(out.items.size());
+    {
+        size_t iw = 0, in = 0;
+        double dw = 0, dn = 0;                     // cost already emitted per kind
+        while (iw < wide_ix.size() || in < narrow_ix.size()) {
+            bool take_wide;
+            if (iw >= wide_ix.size()) take_wide = false;
+            else if (in >= narrow_ix.size()) take_wide = true;
+            else take_wide = dw * narrow_cost <= dn * wide_cost;      // the kind that lags behind its share
+            const int32_t idx = take_wide ? wide_ix[iw++] : narrow_ix[in++];
+            const Item& it = out.items[idx];
+            const double keys = it.kv_end - it.kv_begin;
+            (take_wide ? dw : dn) += take_wide ? keys * 4 : keys;
+            sorted.push_back(it);
+        }
+    }
     out.items.swap(sorted);
 
     // 5. byte layout

@@ -116,5 +116,7 @@ def test_planner_kinds_and_split_policy():
     assert np.array_equal(a, b)
     keys = (a[:, 8] - a[:, 7]).astype(np.int64)
     wide = a[:, 1] == 0
-    cost = np.where(wide, 4 * keys, keys)
-    assert np.all(np.diff(cost) <= 0)            # longest first
+    assert np.all(np.diff(keys[wide]) <= 0) and np.all(np.diff(keys[~wide]) <= 0)     # longest first within a kind
+    # the two kinds are interleaved: both appear in every quarter of the launch order
+    for part in np.array_split(wide, 4):
+        assert part.any() and (~part).any()
