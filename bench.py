@@ -213,7 +213,7 @@ def main():
             C, L = W.config_lengths(3, part={"decode": "decode", "prefill3": "prefill", "mixed": "all"}[part])
             d3 = device_batch(torch, A, W, C, L, sh3, seed=W.BASE_SEED + 3)
             fn = make_runner(torch, A, d3, "mixed")
-            ms3 = time_calls(torch, fn, 20, 3)
+            ms3 = time_calls(torch, fn, 20, 5)
             kt3 = kernel_times(torch, A, fn, 10)
             by = bytes_of(C, L, sh3["Hq"], sh3["Hkv"], sh3["d"], sh3["P"])
             fl3 = flops_of(C, L, sh3["Hq"], sh3["d"])

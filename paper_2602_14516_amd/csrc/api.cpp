@@ -99,6 +99,17 @@ thread_local hipEvent_t t_ev[4] = {nullptr, nullptr, nullptr, nullptr};   // app
 thread_local bool t_valid = false, t_has_append = false;
 
 hipError_t take_slot(size_t bytes, Slot** out) {
+    static bool primed = false;
+    if (!primed) {                            // allocate the whole ring once, not one slot per call
+        primed = true;
+        for (int i = 0; i < RING; ++i) {
+            if (hipHostMalloc(&g_ring[i].host, 1 << 20, hipHostMallocDefault) != hipSuccess) {
+                g_ring[i].host = nullptr;
+                break;
+            }
+            g_ring[i].cap = 1 << 20;
+        }
+    }
     Slot& s = g_ring[g_next];
     g_next = (g_next + 1) % RING;
     hipError_t e;
@@ -114,7 +125,7 @@ hipError_t take_slot(size_t bytes, Slot** out) {
             s.host = nullptr;
             s.cap = 0;
         }
-        size_t cap = 1 << 16;
+        size_t cap = 1 << 20;                 // 1 MiB covers ~30 k work items: regrowth is rare
         while (cap < bytes) cap <<= 1;
         e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
         if (e != hipSuccess) return e;
