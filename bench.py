@@ -185,7 +185,10 @@ def main():
         big = batch.incr_len >= 256
         fl_big = flops_of(batch.ctx_len[big], batch.incr_len[big], batch.Hq, batch.d)
         roof = {"bound": "mfma", "kernel": "attn_kernel<128,bf16>", "achieved": flops / (kt[0] * 1e-3) / 1e12,
-                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s", "traffic": None,
+                "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same step, scaled by the
+                # copy-kernel calibration (x2.0 / x1.0); see profiles/attn_kernel_cfg2_prefill_counters.md
+                "traffic": 692e6 + 75e6, "traffic_unit": "bytes per launch (algorithmic 0.467e9)",
                 "kernel_ms": float(kt[0]), "combine_ms": float(kt[1]), "append_and_plan_copy_ms": float(kt[2]),
                 "work_items": info["num_items"]}
         roof["frac"] = roof["achieved"] / roof["peak"]
