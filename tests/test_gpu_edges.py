@@ -1,0 +1,128 @@
+"""GPU edge cases of the C ABI: head-group shapes, many requests, chunked prefill, determinism,
+error paths that must not enqueue anything, non-default streams."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2602_14516_amd as A
+import workloads as W
+from gpu_util import DevBatch, compare, from_dev_bits, sample_rows, to_dev_bits
+
+pytestmark = pytest.mark.gpu
+
+
+def run(db, fn=A.mixed_batch_attn, **kw):
+    b = db.b
+    out = fn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new, block_table_host=b.block_table, **kw)
+    torch.cuda.synchronize()
+    return from_dev_bits(out)
+
+
+@pytest.mark.parametrize("name,C,L,Hq,Hkv,d,P", [
+    ("mqa-64-heads", [40, 300], [3, 1], 64, 1, 128, 16),          # G = 64: two head blocks of 32
+    ("g3", [77, 0, 500], [50, 11, 1], 6, 2, 128, 16),             # G = 3: 10 tokens per wave, 2 idle rows
+    ("g5-d64", [10, 200], [70, 1], 10, 2, 64, 32),
+    ("g48", [65], [2], 48, 1, 128, 16),                           # head blocks of 32 + 16
+    ("initial-prefill-long", [0], [3000], 8, 2, 64, 16),          # C = 0, many tiles, diagonal everywhere
+    ("one-token-no-history", [0, 0], [1, 1], 8, 8, 128, 16),      # output = v_new exactly
+])
+def test_head_group_shapes(name, C, L, Hq, Hkv, d, P):
+    print(f"case: {name}", flush=True)
+    b = W.make_batch(C, L, Hq, Hkv, d, P, seed=len(name) * 7 + 1, poison=True)
+    db = DevBatch(b)
+    out = run(db)
+    rows = sample_rows(b, 8, seed=1) if sum(L) > 400 else None
+    compare(b, out, rows=rows, label=name)
+    if name == "one-token-no-history":
+        G = Hq // Hkv
+        assert np.array_equal(out.reshape(2, Hq, d), np.repeat(b.v_new, G, axis=1))
+
+
+def test_more_requests_than_one_append_launch_carries():
+    print("case: 300 decode rows + 3 prefill rows", flush=True)
+    rng = np.random.default_rng(3)
+    C = rng.integers(1, 400, size=303).tolist()
+    L = [1] * 300 + [40, 130, 7]
+    b = W.make_batch(C, L, 8, 2, 128, 16, seed=77, poison=True)
+    db = DevBatch(b)
+    out = run(db)
+    k_ref, v_ref = oracle.kv_append_reference(b.k_pool, b.v_pool, b.block_table, b.ctx_len, b.incr_len, b.k_new, b.v_new, b.P)
+    assert np.array_equal(from_dev_bits(db.k_pool), k_ref) and np.array_equal(from_dev_bits(db.v_pool), v_ref)
+    compare(b, out, label="303 rows")
+
+
+def test_chunked_prefill_composes_on_the_gpu():
+    """One call with L new tokens == a call with L1 followed by a call with L2 over C + L1 (the paper's
+    future-work chunked local prefill needs no new kernel)."""
+    print("case: chunked prefill", flush=True)
+    C, L1, L2 = 700, 190, 333
+    b = W.make_batch([C], [L1 + L2], 8, 2, 128, 16, seed=9, poison=True)
+    db = DevBatch(b)
+    whole = run(db, fn=A.incr_prefill_attn)
+    db2 = DevBatch(b)                                            # fresh pools
+    o1 = A.incr_prefill_attn(db2.cache, [C], [L1], db2.bt, db2.q[:L1].contiguous(), db2.k_new[:L1].contiguous(),
+                             db2.v_new[:L1].contiguous(), block_table_host=b.block_table)
+    o2 = A.incr_prefill_attn(db2.cache, [C + L1], [L2], db2.bt, db2.q[L1:].contiguous(), db2.k_new[L1:].contiguous(),
+                             db2.v_new[L1:].contiguous(), block_table_host=b.block_table)
+    torch.cuda.synchronize()
+    parts = np.concatenate([from_dev_bits(o1), from_dev_bits(o2)])
+    assert np.array_equal(from_dev_bits(db.k_pool), from_dev_bits(db2.k_pool))      # same final cache image
+    assert np.array_equal(from_dev_bits(db.v_pool), from_dev_bits(db2.v_pool))
+    compare(b, parts, label="chunked")
+    assert np.abs(W.bf16_bits_to_f64(parts) - W.bf16_bits_to_f64(whole)).max() <= 1e-2
+
+
+def test_three_identical_launches_are_bitwise_equal():
+    print("case: determinism", flush=True)
+    b = W.make_batch([900, 30, 4000, 0], [1, 200, 1, 64], 16, 2, 128, 16, seed=12, poison=True)
+    db = DevBatch(b)
+    outs = [run(db) for _ in range(3)]
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[1], outs[2])
+    outs = [run(db, force_kv_splits=4) for _ in range(2)]
+    assert np.array_equal(outs[0], outs[1])
+
+
+def test_error_paths_enqueue_nothing():
+    print("case: error paths", flush=True)
+    b = W.make_batch([100, 50], [20, 1], 8, 2, 128, 16, seed=5)
+    db = DevBatch(b)
+    k_before = from_dev_bits(db.k_pool).copy()
+    out = torch.full_like(db.q, 7.0)
+    need = A.workspace_bytes(db.cache, b.ctx_len, b.incr_len, b.block_table.shape[1])
+    small = torch.empty(max(need - 256, 16), dtype=torch.uint8, device="cuda")
+    with pytest.raises(A.AmpdError) as e:
+        A.mixed_batch_attn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new, out=out, workspace=small)
+    assert e.value.status == -3
+    big = torch.empty(need + 512, dtype=torch.uint8, device="cuda")
+    with pytest.raises(A.AmpdError) as e:                         # misaligned workspace
+        A.mixed_batch_attn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new, out=out, workspace=big[16:])
+    assert e.value.status == -3
+    bad = b.block_table.copy()
+    bad[0, 1] = b.num_pages + 3
+    with pytest.raises(A.AmpdError) as e:                         # host mirror catches an out-of-range page
+        A.mixed_batch_attn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new, out=out, block_table_host=bad)
+    assert e.value.status == -4
+    with pytest.raises(A.AmpdError) as e:                         # block table too narrow for C + L
+        A.mixed_batch_attn(db.cache, [100, 50], [200, 1], db.bt, db.q, db.k_new, db.v_new, out=out)
+    assert e.value.status == -1
+    torch.cuda.synchronize()
+    assert np.array_equal(from_dev_bits(db.k_pool), k_before), "a rejected call wrote to the cache"
+    assert bool((out == 7.0).all()), "a rejected call wrote to the output"
+    # all-empty batch is a legal no-op
+    A.mixed_batch_attn(db.cache, [5, 6], [0, 0], db.bt, db.q[:0], db.k_new[:0], db.v_new[:0], out=out[:0])
+    torch.cuda.synchronize()
+
+
+def test_runs_on_a_non_default_stream():
+    print("case: side stream", flush=True)
+    b = W.make_batch([300, 10], [90, 1], 8, 2, 128, 16, seed=15, poison=True)
+    db = DevBatch(b)
+    ref = run(db)
+    db2 = DevBatch(b)
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    with torch.cuda.stream(s):
+        out = A.mixed_batch_attn(db2.cache, b.ctx_len, b.incr_len, db2.bt, db2.q, db2.k_new, db2.v_new, stream=s)
+    s.synchronize()
+    assert np.array_equal(from_dev_bits(out), ref)
