@@ -134,6 +134,51 @@ def cpu_baseline(W, batch, budget_s=15.0):
                       f"({fl / 1e9:.1f} GFLOP of causal pairs in {dt:.1f} s, incl. the fp64 gather of their K/V)"}
 
 
+def trace_replay(torch, A, W, max_ticks=None):
+    """Configuration 5: replay a multi-round session trace (32 sessions x 8 rounds, tool outputs of
+    lognormal length, 64-256 decode steps per round) through ONE persistent fp8-e4m3 page pool, one
+    ampd_mixed_batch_attn call per tick.  Tensors are slices of one device-resident random buffer
+    (timing only; parity of this path is covered by tests/test_gpu_fp8.py)."""
+    tr = W.make_trace_schedule(W.BASE_SEED + 5)
+    Hq, Hkv, d, P = tr.Hq, tr.Hkv, tr.d, tr.P
+    k_pool = torch.zeros(tr.num_pages, Hkv, P, d, dtype=torch.uint8, device="cuda")
+    v_pool = torch.zeros_like(k_pool)
+    ks = torch.ones(tr.num_pages, Hkv, dtype=torch.float32, device="cuda")
+    vs = torch.ones_like(ks)
+    cache = A.KVCache(Hq, Hkv, d, P, k_pool, v_pool, 1.0 / np.sqrt(d), ks, vs, kv_dtype=1)
+    ticks = tr.ticks if max_ticks is None else tr.ticks[:max_ticks]
+    max_rows = max(int(t.incr_len.sum()) for t in ticks)
+    gen = torch.Generator(device="cuda").manual_seed(5)
+    rnd = torch.randn(max_rows * (Hq + 2 * Hkv) * d + 4096, device="cuda", generator=gen).to(torch.bfloat16)
+    bt_full = torch.from_numpy(tr.block_table).cuda()
+    bts = [bt_full[torch.from_numpy(t.sessions.astype(np.int64)).cuda()].contiguous() for t in ticks]
+    ws_need = max(A.workspace_bytes(cache, t.ctx_len, t.incr_len, tr.block_table.shape[1]) for t in ticks[::16] + [max(ticks, key=lambda x: int(x.incr_len.sum()))])
+    ws = torch.empty(4 * ws_need + (1 << 20), dtype=torch.uint8, device="cuda")
+    out = torch.empty(max_rows, Hq, d, dtype=torch.bfloat16, device="cuda")
+    flops = by = 0
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i, t in enumerate(ticks):
+        n = int(t.incr_len.sum())
+        q = rnd[:n * Hq * d].view(n, Hq, d)
+        k = rnd[n * Hq * d:n * (Hq + Hkv) * d].view(n, Hkv, d)
+        v = rnd[n * (Hq + Hkv) * d:n * (Hq + 2 * Hkv) * d].view(n, Hkv, d)
+        A.mixed_batch_attn(cache, t.ctx_len, t.incr_len, bts[i], q, k, v, out=out[:n], workspace=ws)
+        flops += flops_of(t.ctx_len, t.incr_len, Hq, d)
+        by += bytes_of(t.ctx_len, t.incr_len, Hq, Hkv, d, P, kvb=1) + int((2 * 4 * Hkv * ((t.ctx_len.astype(np.int64) + t.incr_len + P - 1) // P)).sum())
+    e1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    gpu = e0.elapsed_time(e1) * 1e-3
+    return {"ticks": len(ticks), "sessions": tr.num_sessions, "tokens_appended": int(sum(int(t.incr_len.sum()) for t in ticks)),
+            "pool_pages": tr.num_pages, "kv_dtype": "fp8-e4m3 + fp32 scale per (page, head)",
+            "wall_s": wall, "stream_span_s": gpu, "algorithmic_TFLOP": flops / 1e12, "algorithmic_GB": by / 1e9,
+            "TFLOPs": flops / wall / 1e12, "GBps": by / wall / 1e9, "calls_per_s": len(ticks) / wall,
+            "note": "one Python-driven C-ABI call per tick: the replay is bound by host call overhead, not by the kernels"}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,7 +186,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -155,6 +200,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.only == "trace":
+        print(json.dumps({"only": "trace", **trace_replay(torch, A, W)}))
+        return
 
     if args.only == "copycal":
         x = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
@@ -234,6 +283,10 @@ def main():
             return
         mixed["fused_vs_separate"] = (mixed["decode"]["ms_per_step"] + mixed["prefill3"]["ms_per_step"]) / mixed["mixed"]["ms_per_step"]
 
+    trace = None
+    if not args.no_mixed:
+        trace = trace_replay(torch, A, W)
+
     cpu = None
     if not args.no_cpu_baseline:
         cpu = cpu_baseline(W, batch)
@@ -247,7 +300,7 @@ def main():
                                "L~U[64,1024], page 16, bf16; step = ampd_incr_prefill_attn (append + attention + combine)",
                    "sum_L": int(batch.incr_len.sum()), "sum_T": int((batch.ctx_len + batch.incr_len).sum()),
                    "algorithmic_TFLOP": flops / 1e12, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
-        "roofline": roof, "cpu_baseline": cpu, "mixed": mixed,
+        "roofline": roof, "cpu_baseline": cpu, "mixed": mixed, "trace": trace,
     }
     print(json.dumps(line))
 

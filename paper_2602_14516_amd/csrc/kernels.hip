@@ -51,45 +51,10 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 #define LDS_PTR(T, p) ((__attribute__((address_space(3))) T*)(uintptr_t)(p))
 #define GLOBAL_PTR(p) ((const __attribute__((address_space(1))) void*)(p))
 
-// Build-time experiment switches (defaults = the shipped configuration).
-#ifndef AMPD_PIPE
-#define AMPD_PIPE 0        // software-pipelined 64-key tile inside a wave
-#endif
-#ifndef AMPD_SGB
-#define AMPD_SGB 0         // explicit MFMA / VALU issue interleave hints
-#endif
-#ifndef AMPD_TWOLOOP
-#define AMPD_TWOLOOP 1     // separate unmasked / masked tile loops
-#endif
-#ifndef AMPD_DMA
-#define AMPD_DMA 1         // direct global -> LDS loads for bf16 wide tiles
-#endif
-#ifndef AMPD_EXPERIMENT
-#define AMPD_EXPERIMENT 0  // timing experiments with WRONG results: 1 = no K/V loads after the first tile, 2 = no compute
-#endif
-#ifndef AMPD_NT
-#define AMPD_NT 1          // non-temporal K/V loads on the register-staged (narrow item) path
-#endif
-#ifndef AMPD_SWAP
-#define AMPD_SWAP 1        // v_permlane32_swap instead of an LDS permute for the lane^32 exchange
-#endif
-#ifndef AMPD_DOT2
-#define AMPD_DOT2 0        // row sums from the bf16 probabilities with v_dot2c_f32_bf16
-#endif
-#ifndef AMPD_PRIO
-#define AMPD_PRIO 0        // raise the wave priority while it feeds the matrix pipe
-#endif
-
 constexpr int WG = 256;                 // append / combine kernels
 constexpr int AWG = 64 * ATTN_WAVES;    // attention kernel: 8 waves, one workgroup per CU
-#ifndef AMPD_KT
-#define AMPD_KT 128
-#endif
-#ifndef AMPD_NSTAGE
-#define AMPD_NSTAGE 2
-#endif
-constexpr int KT = AMPD_KT;             // keys per LDS stage of a wide item (one barrier per stage)
-constexpr int NSTAGE = AMPD_NSTAGE;     // LDS ring of K/V stages for wide items
+constexpr int KT = 128;                 // keys per LDS stage of a wide item (one barrier per stage)
+constexpr int NSTAGE = 2;               // LDS ring of K/V stages for wide items
 constexpr float NEG_INF = -__builtin_inff();
 
 template <int D>
@@ -117,28 +82,12 @@ __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_ex
 // r0 = {x[0..31], x[0..31]} and r1 = {x[32..63], x[32..63]} (by destination lane halves), so
 // op(r0, r1) is op(x[l], x[l^32]) in every lane.
 __device__ __forceinline__ float max_xor32(float x) {
-#if AMPD_SWAP
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-#else
-    return fmaxf(x, __shfl_xor(x, 32, 64));
-#endif
 }
 __device__ __forceinline__ float sum_xor32(float x) {
-#if AMPD_SWAP
     const u32x2 r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-#else
-    return x + __shfl_xor(x, 32, 64);
-#endif
-}
-__device__ __forceinline__ void mfma_priority(bool on) {
-#if AMPD_PRIO
-    if (on)
-        __builtin_amdgcn_s_setprio(1);
-    else
-        __builtin_amdgcn_s_setprio(0);
-#endif
 }
 
 // 8 stored elements -> 8 bf16 (as a 16-byte vector) for LDS.
@@ -150,11 +99,7 @@ struct RawChunk<KV_BF16> {
     static constexpr int ES = 2;                      // bytes per stored element
     __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
-#if AMPD_NT
         v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + lane_off));   // streamed once: do not displace L2 lines
-#else
-        v = *reinterpret_cast<const u32x4*>(base + lane_off);
-#endif
     }
     __device__ __forceinline__ u32x4 widen(float) const { return v; }
 };
@@ -257,10 +202,9 @@ __device__ __forceinline__ float rowmax32(const f32x16& S) {
     return max_xor32(mx);
 }
 
-// Raise the reference maximum to cover mx (log2 domain) and rescale O, l and, if given, the
-// not yet accumulated probabilities of the previous block.
+// Raise the reference maximum to cover mx (log2 domain) and rescale O and l.
 template <int D>
-__device__ __forceinline__ void raise_reference(WaveAcc<D>& st, float mx, bf16x8* pending) {
+__device__ __forceinline__ void raise_reference(WaveAcc<D>& st, float mx) {
     const float m_new = fmaxf(st.m, mx);
     const float alpha = fast_exp2(st.m - (m_new == NEG_INF ? 0.0f : m_new));
     st.l *= alpha;
@@ -268,36 +212,18 @@ __device__ __forceinline__ void raise_reference(WaveAcc<D>& st, float mx, bf16x8
     for (int db = 0; db < Geo<D>::NDB; ++db)
 #pragma unroll
         for (int i = 0; i < 16; ++i) st.O[db][i] *= alpha;
-    if (pending) {
-#pragma unroll
-        for (int h = 0; h < 2; ++h)
-#pragma unroll
-            for (int i = 0; i < 8; ++i) pending[h][i] = (__bf16)((float)pending[h][i] * alpha);
-    }
     st.m = m_new;
 }
 
 // p = 2^(S*c - m); returns this lane's sum; P = bf16(p) as the two B operands of the second product
 __device__ __forceinline__ float exp32(const f32x16& S, float c, float m_use, bf16x8 (&P)[2]) {
     float psum = 0.0f;
-#if AMPD_DOT2
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int i = 0; i < 16; i += 2) {
-        const bf16x2 pp = {(__bf16)fast_exp2(__builtin_fmaf(S[i], c, -m_use)),
-                           (__bf16)fast_exp2(__builtin_fmaf(S[i + 1], c, -m_use))};
-        psum = __builtin_amdgcn_fdot2_f32_bf16(pp, ones, psum, false);     // sum of the rounded values
-        P[i >> 3][i & 7] = pp[0];
-        P[i >> 3][(i & 7) + 1] = pp[1];
-    }
-#else
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const float pv = fast_exp2(__builtin_fmaf(S[i], c, -m_use));
         psum += pv;
         P[i >> 3][i & 7] = (__bf16)pv;
     }
-#endif
     return psum;
 }
 
@@ -335,77 +261,32 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
     qk32<D>(kl, Q, S, lane);
     if (masked) mask32(S, rel);                          // wave-uniform
     const float mx = rowmax32(S) * c;
-    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx, nullptr);
+    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx);
     st.l += exp32(S, c, st.m == NEG_INF ? 0.0f : st.m, P);
     pv32<D>(vl, P, st, lane);
 }
 
-// One 64-key tile of a wide item, software-pipelined inside the wave so that the matrix
-// pipe and the vector ALU work on different 32-key halves at the same time:
-//   S0 = K0 Q^T | max(S0) | S1 = K1 Q^T  ||  P0 = exp(S0) | max(S1) | O += V0 P0  ||  P1 = exp(S1) | O += V1 P1
+// One 64-key tile of a wide item: both 32-key halves share one maximum check, so that the
+// compiler can run the second half's exponentials in the shadow of the first half's O += V P.
 template <int D, bool MASK>
 __device__ __forceinline__ void tile64(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
                                        float c, int rel, int lane) {
     using G_ = Geo<D>;
     f32x16 S0, S1;
     bf16x8 P0[2], P1[2];
-#if AMPD_PIPE
-    qk32<D>(kl, Q, S0, lane);
-    if (MASK) mask32(S0, rel);
-    const float mx0 = rowmax32(S0) * c;
-    if (__any(mx0 > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx0, nullptr);
-    {
-        const float m_use = st.m == NEG_INF ? 0.0f : st.m;
-        qk32<D>(kl + G_::B32, Q, S1, lane);
-        st.l += exp32(S0, c, m_use, P0);
-#if AMPD_SGB
-        // issue order: one matrix instruction, then the vector work that fits in its shadow
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int i = 0; i < G_::NKK; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < G_::NKK - 4) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 56 / G_::NKK, 0);
-        }
-#endif
-    }
-    if (MASK) mask32(S1, rel - 32);
-    const float mx1 = rowmax32(S1) * c;
-    if (__any(mx1 > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx1, P0);
-    {
-        const float m_use = st.m == NEG_INF ? 0.0f : st.m;
-        pv32<D>(vl, P0, st, lane);
-        st.l += exp32(S1, c, m_use, P1);
-#if AMPD_SGB
-        __builtin_amdgcn_sched_group_barrier(0x100, 4, 0);
-#pragma unroll
-        for (int i = 0; i < 2 * G_::NDB; ++i) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            if (i < 2 * G_::NDB - 2) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 56 / (2 * G_::NDB), 0);
-        }
-#endif
-    }
-    pv32<D>(vl + G_::B32, P1, st, lane);
-#else
-    mfma_priority(true);
     qk32<D>(kl, Q, S0, lane);
     qk32<D>(kl + G_::B32, Q, S1, lane);
-    mfma_priority(false);
     if (MASK) {
         mask32(S0, rel);
         mask32(S1, rel - 32);
     }
     const float mx = fmaxf(rowmax32(S0), rowmax32(S1)) * c;
-    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx, nullptr);
+    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx);
     const float m_use = st.m == NEG_INF ? 0.0f : st.m;
     st.l += exp32(S0, c, m_use, P0);
     st.l += exp32(S1, c, m_use, P1);
-    mfma_priority(true);
     pv32<D>(vl, P0, st, lane);
     pv32<D>(vl + G_::B32, P1, st, lane);
-    mfma_priority(false);
-#endif
 }
 
 // Load the B operand (Q^T) of one wave: lane holds row lane%32, d = kk*16 + (lane/32)*8 .. +8.
@@ -624,7 +505,7 @@ __device__ __forceinline__ void dma_wait_tiles(int tiles) {
 template <int D, int KVT>
 __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
     using G_ = Geo<D>;
-    constexpr bool DMA = KVT == KV_BF16 && AMPD_DMA;
+    constexpr bool DMA = KVT == KV_BF16;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int tqw = 32 / ic.gn;                            // tokens per wave
     const int row = lane & 31;
@@ -658,10 +539,10 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
         for (int h = 0; h < KT / 64; ++h) {
             const int kbase = k_lo + t * KT + h * 64;
             // skip 64-key halves that lie beyond the key range or that every row of the wave masks
-            if (AMPD_EXPERIMENT != 2 && wave_active && kbase <= w_last && kbase < ic.kv_end) {
+            if (wave_active && kbase <= w_last && kbase < ic.kv_end) {
                 const int rel = lim - kbase - 4 * (lane >> 5);
-                tile64<D, decltype(masked)::value>(stage + h * 2 * G_::B32, stage + G_::KTILE + h * 2 * G_::B32, Q, st,
-                                                   p.c_log2, rel, lane);
+                    tile64<D, decltype(masked)::value>(stage + h * 2 * G_::B32, stage + G_::KTILE + h * 2 * G_::B32, Q, st,
+                                                       p.c_log2, rel, lane);
             }
         }
     };
@@ -681,7 +562,7 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
         dma_wait_tiles<PT>(in_flight_after(-1));
         __syncthreads();
         auto step = [&](int t, auto masked) {
-            if (t + AHEAD < ntiles && AMPD_EXPERIMENT != 1) issue(t + AHEAD);
+            if (t + AHEAD < ntiles) issue(t + AHEAD);
             compute(t, smem + (t % NSTAGE) * G_::WIDE_STAGE, masked);
             dma_wait_tiles<PT>(in_flight_after(t));         // tile t+1 has landed in LDS
             __syncthreads();
@@ -753,7 +634,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
         }
         const int rel = lim - kbase - 4 * (lane >> 5);
-        if (AMPD_EXPERIMENT != 2) block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
+        block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
     }
     // merge the waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
     const float ltot = sum_xor32(st.l);
