@@ -179,6 +179,62 @@ def trace_replay(torch, A, W, max_ticks=None):
             "note": "one Python-driven C-ABI call per tick: the replay is bound by host call overhead, not by the kernels"}
 
 
+def model_sweep(torch, A, W):
+    """Measure T_pre(l_hist, l_incr) (one request, configuration-2 layer shape) and T_dec(b, sum C)
+    (configuration-3 layer shape) as whole-step times of the C-ABI calls and fit the piecewise
+    alpha-beta model of paper Section 3 to them."""
+    from paper_2602_14516_amd.perf_model import fit_piecewise_alpha_beta, prefill_flops, decode_bytes
+    res = {"T_pre": [], "T_dec": []}
+    sh = W.CONFIG_SHAPES[2]
+    for l_hist in (0, 1024, 4096, 16384, 65536):
+        for l_incr in (16, 64, 256, 1024, 4096):
+            C, L = np.array([l_hist], np.int32), np.array([l_incr], np.int32)
+            db = device_batch(torch, A, W, C, L, sh, seed=1)
+            fn = make_runner(torch, A, db, "prefill")
+            ms = time_calls(torch, fn, 20, 3)
+            res["T_pre"].append((l_hist, l_incr, ms * 1e-3))
+            del db, fn
+    sh = W.CONFIG_SHAPES[3]
+    g = np.random.default_rng(1)
+    for b in (1, 8, 32, 96, 256):
+        for cmean in (1024, 4096, 16384):
+            C = g.integers(cmean // 2, cmean * 3 // 2, size=b, endpoint=True).astype(np.int32)
+            L = np.ones(b, np.int32)
+            db = device_batch(torch, A, W, C, L, sh, seed=2)
+            fn = make_runner(torch, A, db, "mixed")
+            ms = time_calls(torch, fn, 20, 3)
+            res["T_dec"].append((b, int(C.sum()), ms * 1e-3))
+            del db, fn
+            torch.cuda.empty_cache()
+    from paper_2602_14516_amd.perf_model import fit_alpha_beta_family
+    pre = np.array(res["T_pre"], dtype=np.float64)
+    fam_p = fit_alpha_beta_family(pre[:, 1], pre[:, 0], pre[:, 2])                 # one line in l_hist per l_incr
+    err_p = np.abs(fam_p(pre[:, 1], pre[:, 0]) - pre[:, 2]) / pre[:, 2]
+    x = prefill_flops(pre[:, 0], pre[:, 1], W.CONFIG_SHAPES[2]["Hq"], W.CONFIG_SHAPES[2]["d"])
+    mp = fit_piecewise_alpha_beta(x, pre[:, 2], segments=3)                        # one scalar size (FLOPs), 3 segments
+    dec = np.array(res["T_dec"], dtype=np.float64)
+    fam_d = fit_alpha_beta_family(dec[:, 0], dec[:, 1], dec[:, 2])                 # one line in sum C per batch size
+    err_d = np.abs(fam_d(dec[:, 0], dec[:, 1]) - dec[:, 2]) / dec[:, 2]
+    s3 = W.CONFIG_SHAPES[3]
+    xb = decode_bytes(dec[:, 1], dec[:, 0], s3["Hq"], s3["Hkv"], s3["d"])
+    md = fit_piecewise_alpha_beta(xb, dec[:, 2], segments=3)
+    return {"only": "model",
+            "T_pre": {"per_l_incr_lines_in_l_hist": {"l_incr": fam_p.buckets.tolist(), "alpha_s": fam_p.alpha.tolist(),
+                                                     "beta_s_per_token": fam_p.beta.tolist(),
+                                                     "rel_err_mean": float(err_p.mean()), "rel_err_max": float(err_p.max())},
+                      "piecewise_in_flops": {"knots": mp.knots.tolist(), "alpha_s": mp.alpha.tolist(), "beta_s_per_flop": mp.beta.tolist(),
+                                             "rel_err_mean": float(mp.rel_error(x, pre[:, 2]).mean()),
+                                             "rel_err_max": float(mp.rel_error(x, pre[:, 2]).max())},
+                      "points_l_hist_l_incr_seconds": [(int(a), int(b_), float(t)) for a, b_, t in res["T_pre"]]},
+            "T_dec": {"per_batch_lines_in_sum_ctx": {"b": fam_d.buckets.tolist(), "alpha_s": fam_d.alpha.tolist(),
+                                                     "beta_s_per_token": fam_d.beta.tolist(),
+                                                     "rel_err_mean": float(err_d.mean()), "rel_err_max": float(err_d.max())},
+                      "piecewise_in_bytes": {"knots": md.knots.tolist(), "alpha_s": md.alpha.tolist(), "beta_s_per_byte": md.beta.tolist(),
+                                             "rel_err_mean": float(md.rel_error(xb, dec[:, 2]).mean()),
+                                             "rel_err_max": float(md.rel_error(xb, dec[:, 2]).max())},
+                      "points_b_sum_ctx_seconds": [(int(a), int(b_), float(t)) for a, b_, t in res["T_dec"]]}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -186,7 +242,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -200,6 +256,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.only == "model":
+        print(json.dumps(model_sweep(torch, A, W)))
+        return
 
     if args.only == "trace":
         print(json.dumps({"only": "trace", **trace_replay(torch, A, W)}))

@@ -235,7 +235,9 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     if (g_timing) HIP_TRY(hipEventRecord(t_ev[1], st));
     HIP_TRY(launch_attn(p, c->head_dim, kvt, (int)plan.items.size(), st));
     if (g_timing) HIP_TRY(hipEventRecord(t_ev[2], st));
-    HIP_TRY(launch_combine(p, c->head_dim, (int)plan.combs.size(), st));
+    int comb_rows = 0;
+    for (const CombItem& ci : plan.combs) comb_rows = std::max(comb_rows, ci.nq * ((ci.heads >> 16) & 0xff));
+    HIP_TRY(launch_combine(p, c->head_dim, (int)plan.combs.size(), comb_rows, st));
     if (g_timing) {
         HIP_TRY(hipEventRecord(t_ev[3], st));
         t_valid = true;

@@ -42,7 +42,8 @@ struct AppendParams {
 // h_src: pinned, device-visible host memory; bytes is rounded up to 16
 hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream_t st);
 hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st);
-hipError_t launch_combine(const AttnParams& p, int D, int ncombs, hipStream_t st);
+// max_rows: the largest nq * heads among the split tiles (sizes the second grid dimension)
+hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);
 
 }  // namespace ampd

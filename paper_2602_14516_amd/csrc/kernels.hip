@@ -741,15 +741,20 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
 // combine: merge the split-KV partials of one query tile
 //   m = max_s m_s;  l = sum_s l_s 2^(m_s - m);  O = sum_s O_s 2^(m_s - m) / l
 
+constexpr int COMB_ROWS = 16;          // query rows per combine workgroup
+
 template <int D>
 __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
     const CombItem ci = p.combs[blockIdx.x];
     const int kvh = ci.heads & 0xff, g0 = (ci.heads >> 8) & 0xff, gn = (ci.heads >> 16) & 0xff;
-    const ReqInfo ri = p.reqs[ci.req];
     const int rows = ci.nq * gn;
+    const int r0 = blockIdx.y * COMB_ROWS;                  // grid.y covers the tallest tile (256 rows)
+    if (r0 >= rows) return;
+    const ReqInfo ri = p.reqs[ci.req];
+    const int nr = min(COMB_ROWS, rows - r0);
     constexpr int QPR = D / 4;                         // float4 groups per row
-    for (int u = threadIdx.x; u < rows * QPR; u += WG) {
-        const int r = u / QPR, dq = (u % QPR) * 4;
+    for (int u = threadIdx.x; u < nr * QPR; u += WG) {
+        const int r = r0 + u / QPR, dq = (u % QPR) * 4;
         float mall = NEG_INF;
         for (int s = 0; s < ci.nsplit; ++s) {
             const float* ml = p.partial + ci.part_off + (int64_t)s * ci.part_stride + (int64_t)rows * D + r * 2;
@@ -933,12 +938,13 @@ hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStrea
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_combine(const AttnParams& p, int D, int ncombs, hipStream_t st) {
+hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, hipStream_t st) {
     if (ncombs <= 0) return hipSuccess;
+    const dim3 grid(ncombs, (max_rows + COMB_ROWS - 1) / COMB_ROWS);
     if (D == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), dim3(ncombs), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL((combine_kernel<128>), grid, dim3(WG), 0, st, p);
     else
-        hipLaunchKernelGGL((combine_kernel<64>), dim3(ncombs), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL((combine_kernel<64>), grid, dim3(WG), 0, st, p);
     return hipGetLastError();
 }
 

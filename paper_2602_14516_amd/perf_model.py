@@ -1,0 +1,117 @@
+"""Piecewise alpha-beta cost model of the attention path, fitted from measured step times.
+
+The paper's profiler turns measured execution times into cost functions that its planner
+and online scheduler query (paper Section 3, "Offline stage": T_pre(l_hist, l_incr),
+T_dec(b); the alpha-beta form is the latency + size/bandwidth model it cites).  For the
+operator built here the natural "size" is the algorithmic work of a call:
+
+    T_pre(l_hist, l_incr)  ~  alpha_s + beta_s * FLOPs,   FLOPs = 4 d Hq (l_incr l_hist + l_incr (l_incr+1)/2)
+    T_dec(b, sum C)        ~  alpha_s + beta_s * bytes,   bytes = 2 (sum C + b) Hkv d b_kv + ...
+
+with one (alpha_s, beta_s) pair per size segment s (small calls are launch-bound, large calls
+run at the kernel's asymptotic rate).  The paper's T_dec takes only the batch size; the
+measured cost of decode attention is set by the total context, so sum C is kept.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+
+@dataclass
+class PiecewiseAlphaBeta:
+    """t(x) = alpha[s] + beta[s] * x on segment s, segments delimited by `knots` (ascending,
+    len = segments - 1); x below the first knot uses segment 0."""
+    knots: np.ndarray
+    alpha: np.ndarray
+    beta: np.ndarray
+
+    def __call__(self, x):
+        x = np.asarray(x, dtype=np.float64)
+        s = np.searchsorted(self.knots, x, side="right")
+        return self.alpha[s] + self.beta[s] * x
+
+    def rel_error(self, x, t):
+        t = np.asarray(t, dtype=np.float64)
+        return np.abs(self(x) - t) / t
+
+
+def fit_piecewise_alpha_beta(x, t, segments: int = 3, knots=None) -> PiecewiseAlphaBeta:
+    """Least-squares fit of a piecewise alpha-beta model.  Knots default to equal-count
+    quantiles of log(x); every segment needs at least two distinct sizes (else it inherits
+    its neighbour's line)."""
+    x = np.asarray(x, dtype=np.float64)
+    t = np.asarray(t, dtype=np.float64)
+    assert x.shape == t.shape and x.ndim == 1 and x.size >= 2
+    if knots is None:
+        qs = np.linspace(0, 1, segments + 1)[1:-1]
+        knots = np.exp(np.quantile(np.log(np.maximum(x, 1e-30)), qs)) if segments > 1 else np.zeros(0)
+    knots = np.asarray(knots, dtype=np.float64)
+    nseg = len(knots) + 1
+    seg = np.searchsorted(knots, x, side="right")
+    alpha = np.full(nseg, np.nan)
+    beta = np.full(nseg, np.nan)
+    for s in range(nseg):
+        m = seg == s
+        if m.sum() >= 2 and np.ptp(x[m]) > 0:
+            A = np.stack([np.ones(m.sum()), x[m]], axis=1)
+            # relative least squares: every measurement counts equally whatever its size
+            w = 1.0 / t[m]
+            sol, *_ = np.linalg.lstsq(A * w[:, None], t[m] * w, rcond=None)
+            alpha[s], beta[s] = sol
+    for s in range(nseg):                       # segments without enough data copy the nearest fitted one
+        if np.isnan(alpha[s]):
+            ok = np.nonzero(~np.isnan(alpha))[0]
+            assert ok.size, "no segment could be fitted"
+            n = ok[np.argmin(np.abs(ok - s))]
+            alpha[s], beta[s] = alpha[n], beta[n]
+    return PiecewiseAlphaBeta(knots, alpha, beta)
+
+
+def prefill_flops(l_hist, l_incr, Hq: int, d: int):
+    l_hist = np.asarray(l_hist, dtype=np.float64)
+    l_incr = np.asarray(l_incr, dtype=np.float64)
+    return 4.0 * d * Hq * (l_incr * l_hist + l_incr * (l_incr + 1) / 2)
+
+
+def decode_bytes(sum_ctx, b, Hq: int, Hkv: int, d: int, kv_bytes: int = 2):
+    sum_ctx = np.asarray(sum_ctx, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    return 2.0 * (sum_ctx + b) * Hkv * d * kv_bytes + 2 * b * Hkv * d * (2 + kv_bytes) + 2 * b * Hq * d * 2
+
+
+@dataclass
+class AlphaBetaFamily:
+    """One alpha-beta line t = alpha + beta * size per bucket of a second variable (e.g. one line in
+    l_hist per incremental length, one line in sum C per decode batch size); queries between
+    buckets interpolate the two neighbouring lines linearly in log(bucket)."""
+    buckets: np.ndarray
+    alpha: np.ndarray
+    beta: np.ndarray
+
+    def __call__(self, bucket, size):
+        bucket = np.atleast_1d(np.asarray(bucket, dtype=np.float64))
+        size = np.atleast_1d(np.asarray(size, dtype=np.float64))
+        lb = np.log(self.buckets)
+        q = np.clip(np.log(np.maximum(bucket, 1e-30)), lb[0], lb[-1])
+        hi = np.clip(np.searchsorted(lb, q, side="left"), 1, len(lb) - 1) if len(lb) > 1 else np.zeros_like(q, dtype=int)
+        lo = np.maximum(hi - 1, 0)
+        w = np.where(lb[hi] > lb[lo], (q - lb[lo]) / np.where(lb[hi] > lb[lo], lb[hi] - lb[lo], 1.0), 0.0)
+        t_lo = self.alpha[lo] + self.beta[lo] * size
+        t_hi = self.alpha[hi] + self.beta[hi] * size
+        return (1 - w) * t_lo + w * t_hi
+
+
+def fit_alpha_beta_family(bucket, size, t) -> AlphaBetaFamily:
+    bucket = np.asarray(bucket, dtype=np.float64)
+    size = np.asarray(size, dtype=np.float64)
+    t = np.asarray(t, dtype=np.float64)
+    bs = np.unique(bucket)
+    alpha, beta = [], []
+    for b in bs:
+        m = bucket == b
+        fit = fit_piecewise_alpha_beta(size[m], t[m], segments=1)
+        alpha.append(fit.alpha[0])
+        beta.append(fit.beta[0])
+    return AlphaBetaFamily(bs, np.array(alpha), np.array(beta))
