@@ -235,6 +235,51 @@ def model_sweep(torch, A, W):
                       "points_b_sum_ctx_seconds": [(int(a), int(b_), float(t)) for a, b_, t in res["T_dec"]]}}
 
 
+def chunked_local_prefill(torch, A, W):
+    """The paper's first future-work item (Section 7: chunk long local prefills to reduce the blocking of
+    decoding): one decode instance carries 96 decode rows (configuration-3 shape) and receives one
+    incremental prefill of 4096 tokens over 8192 cached ones.  It is executed as 1, 2, 4, 8 or 16 successive
+    mixed-batch calls, each appending one chunk next to one decode step of every other row; the time of
+    one call is what the decode rows experience as inter-token latency."""
+    sh = W.CONFIG_SHAPES[3]
+    Cd, _ = W.config_lengths(3, part="decode")
+    L_total, C_pre = 4096, 8192
+    out = []
+    base = None
+    for nchunks in (1, 2, 4, 8, 16):
+        chunk = L_total // nchunks
+        # lengths of the first call; every later call moves the prefill row by one chunk and the decode rows by one token
+        C = np.concatenate([Cd, [C_pre]]).astype(np.int32)
+        Lmax = np.concatenate([np.full(96, nchunks, np.int32), [L_total]]).astype(np.int32)      # pages for the whole sequence of calls
+        db = device_batch(torch, A, W, C, Lmax, sh, seed=7)
+        calls = []
+        for i in range(nchunks):
+            Ci = np.concatenate([Cd + i, [C_pre + i * chunk]]).astype(np.int32)
+            Li = np.concatenate([np.ones(96, np.int32), [chunk]]).astype(np.int32)
+            n = int(Li.sum())
+            ws = torch.empty(A.workspace_bytes(db["cache"], Ci, Li, db["bt"].shape[1]), dtype=torch.uint8, device="cuda")
+            calls.append((Ci, Li, n, ws))
+
+        def run_all():
+            for Ci, Li, n, ws in calls:
+                A.mixed_batch_attn(db["cache"], Ci, Li, db["bt"], db["q"][:n], db["k_new"][:n], db["v_new"][:n],
+                                   out=db["out"][:n], workspace=ws)
+        ms = time_calls(torch, run_all, 10, 3)
+        rec = {"chunks": nchunks, "chunk_tokens": chunk, "total_ms": ms, "ms_per_call": ms / nchunks}
+        if base is None:
+            base = ms
+        rec["total_vs_unchunked"] = ms / base
+        out.append(rec)
+        del db, calls
+        torch.cuda.empty_cache()
+    # a pure decode step of the same 96 rows, for reference
+    Ld = np.ones(96, np.int32)
+    db = device_batch(torch, A, W, Cd, Ld, sh, seed=7)
+    fn = make_runner(torch, A, db, "mixed")
+    dec = time_calls(torch, fn, 20, 5)
+    return {"only": "chunked", "decode_step_alone_ms": dec, "runs": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -242,7 +287,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -256,6 +301,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.only == "chunked":
+        print(json.dumps(chunked_local_prefill(torch, A, W)))
+        return
 
     if args.only == "model":
         print(json.dumps(model_sweep(torch, A, W)))

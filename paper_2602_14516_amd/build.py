@@ -40,5 +40,21 @@ def build(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
+SCHED_LIB = os.path.join(HERE, "libampd_sched.so")
+SCHED_SRC = os.path.join(CSRC, "sched.cpp")
+SCHED_HDR = os.path.join(INCLUDE, "ampd_sched.h")
+
+
+def build_sched(force: bool = False) -> str:
+    """Compile the host-only scheduling library (no GPU code) with g++."""
+    stale = (not os.path.exists(SCHED_LIB) or
+             os.path.getmtime(SCHED_LIB) < max(os.path.getmtime(SCHED_SRC), os.path.getmtime(SCHED_HDR)))
+    if force or stale:
+        subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-I", INCLUDE,
+                               SCHED_SRC, "-o", SCHED_LIB])
+    return SCHED_LIB
+
+
 if __name__ == "__main__":
+    print(build_sched(force=True))
     print(build(force=True, verbose=True))
