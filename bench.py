@@ -280,6 +280,28 @@ def chunked_local_prefill(torch, A, W):
     return {"only": "chunked", "decode_step_alone_ms": dec, "runs": out}
 
 
+def kv_transfer(torch, A, W):
+    """Pack / unpack of a KV transfer (paper Section 3, T_kv; Eq. 2): the history KV of 16 requests
+    (configuration-2 shape, 77 k tokens) for one destination rank's share of 2 of the 8 KV heads, and for all
+    heads.  HBM-bound copies: bytes moved = 2 x payload (read + write)."""
+    sh = W.CONFIG_SHAPES[2]
+    C, L = W.config_lengths(2)
+    T = (C + L).astype(np.int32)
+    db = device_batch(torch, A, W, T, np.zeros_like(T), sh, seed=9)
+    zero = np.zeros_like(T)
+    out = []
+    for h0, hn in ((0, 8), (2, 2)):
+        n = int(T.sum())
+        kb = torch.empty(n, hn, sh["d"], dtype=torch.bfloat16, device="cuda")
+        vb = torch.empty_like(kb)
+        payload = 2 * n * hn * sh["d"] * 2
+        for name, fn in (("pack", lambda: A.kv_pack(db["cache"], zero, T, db["bt"], h0, hn, kb, vb)),
+                         ("unpack", lambda: A.kv_unpack(db["cache"], zero, T, db["bt"], h0, hn, kb, vb))):
+            ms = time_calls(torch, fn, 20, 3)
+            out.append({"op": name, "heads": hn, "payload_MB": payload / 1e6, "ms": ms, "GBps_read_plus_write": 2 * payload / (ms * 1e-3) / 1e9})
+    return {"only": "kvtransfer", "tokens": int(T.sum()), "runs": out}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -287,7 +309,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -301,6 +323,10 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible; the HIP path has no CPU fallback", file=sys.stderr)
         sys.exit(1)
+
+    if args.only == "kvtransfer":
+        print(json.dumps(kv_transfer(torch, A, W)))
+        return
 
     if args.only == "chunked":
         print(json.dumps(chunked_local_prefill(torch, A, W)))

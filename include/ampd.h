@@ -119,6 +119,19 @@ size_t ampd_workspace_bytes_opts(const ampd_kv_cache *cache, const ampd_batch *b
 ampd_status ampd_kv_append(const ampd_kv_cache *cache, const ampd_batch *batch,
                            const void *k_new, const void *v_new, void *stream);
 
+/* The GPU side of a KV transfer between workers whose parallelism differs (paper Section 3,
+ * T_kv(l_ctx; theta_src, theta_dst); Section 4.1, Eq. 2: history KV to the prefill worker,
+ * incremental KV back): gather tokens [C_r, C_r + L_r) of every row, KV heads
+ * [head_begin, head_begin + head_count) only, from the pages into packed rows
+ * k_out, v_out: DEVICE bf16 [sum L][head_count][d] (the send buffer for the rank that owns those
+ * heads), and the inverse scatter of received rows into pages.  bf16 caches only
+ * (AMPD_ERR_UNSUPPORTED otherwise); bit-exact copies; h_ctx_len is the first token, h_incr_len
+ * the token count of each row.  ampd_kv_unpack over all heads equals ampd_kv_append. */
+ampd_status ampd_kv_pack(const ampd_kv_cache *cache, const ampd_batch *batch, int32_t head_begin,
+                         int32_t head_count, void *k_out, void *v_out, void *stream);
+ampd_status ampd_kv_unpack(const ampd_kv_cache *cache, const ampd_batch *batch, int32_t head_begin,
+                           int32_t head_count, const void *k_in, const void *v_in, void *stream);
+
 /* Append, then causal GQA attention of the L_r new queries of every row over its C_r + L_r
  * keys (prefill with history l_hist = C_r and incremental length l_incr = L_r).
  * q: DEVICE bf16 [sum L][Hq][d];  out: DEVICE bf16 [sum L][Hq][d].

@@ -17,7 +17,7 @@ EXPORTED_SYMBOLS = [
     "ampd_workspace_bytes", "ampd_workspace_bytes_opts", "ampd_kv_append",
     "ampd_incr_prefill_attn", "ampd_mixed_batch_attn", "ampd_incr_prefill_attn_opts",
     "ampd_mixed_batch_attn_opts", "ampd_paged_attn", "ampd_plan_describe", "ampd_plan_items",
-    "ampd_set_timing", "ampd_last_timing", "ampd_status_string", "ampd_version",
+    "ampd_set_timing", "ampd_last_timing", "ampd_status_string", "ampd_version", "ampd_kv_pack", "ampd_kv_unpack",
 ]
 
 AMPD_KV_BF16, AMPD_KV_FP8_E4M3 = 0, 1
@@ -68,6 +68,10 @@ def _load():
     L.ampd_workspace_bytes_opts.argtypes = [cp, bp, op]
     L.ampd_kv_append.restype = i32
     L.ampd_kv_append.argtypes = [cp, bp, vp, vp, vp]
+    for name in ("ampd_kv_pack", "ampd_kv_unpack"):
+        f = getattr(L, name)
+        f.restype = i32
+        f.argtypes = [cp, bp, i32, i32, vp, vp, vp]
     for name in ("ampd_incr_prefill_attn", "ampd_mixed_batch_attn"):
         f = getattr(L, name)
         f.restype = i32
@@ -206,6 +210,24 @@ def kv_append(cache: KVCache, ctx_len, incr_len, block_table, k_new, v_new, *, s
     c = cache.c_struct()
     _check(lib.ampd_kv_append(ctypes.byref(c), ctypes.byref(b), _ptr(k_new), _ptr(v_new), _stream_ptr(stream)),
            "ampd_kv_append")
+
+
+def kv_pack(cache: KVCache, first_token, num_tokens, block_table, head_begin, head_count, k_out, v_out, *, stream=None,
+            block_table_host=None) -> None:
+    """Pages -> packed rows [sum tokens, head_count, d] for KV heads [head_begin, head_begin + head_count)."""
+    b, keep = _batch(first_token, num_tokens, block_table, block_table_host)
+    c = cache.c_struct()
+    _check(lib.ampd_kv_pack(ctypes.byref(c), ctypes.byref(b), int(head_begin), int(head_count), _ptr(k_out), _ptr(v_out),
+                            _stream_ptr(stream)), "ampd_kv_pack")
+
+
+def kv_unpack(cache: KVCache, first_token, num_tokens, block_table, head_begin, head_count, k_in, v_in, *, stream=None,
+              block_table_host=None) -> None:
+    """Packed rows -> pages, the inverse of kv_pack."""
+    b, keep = _batch(first_token, num_tokens, block_table, block_table_host)
+    c = cache.c_struct()
+    _check(lib.ampd_kv_unpack(ctypes.byref(c), ctypes.byref(b), int(head_begin), int(head_count), _ptr(k_in), _ptr(v_in),
+                              _stream_ptr(stream)), "ampd_kv_unpack")
 
 
 def _attn_call(fn_name, cache, ctx_len, incr_len, block_table, q, k_new, v_new, out, workspace, stream,

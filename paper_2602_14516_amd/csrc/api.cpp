@@ -152,8 +152,11 @@ ampd_status ensure_timing_events() {
 
 // ---- launches --------------------------------------------------------------------------------
 
-ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k_new, const void* v_new, hipStream_t st) {
+// mode 0: append (all heads);  1: unpack rows of heads [h0, h0+hn) into pages;  2: pack pages into rows
+ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k_new, const void* v_new, hipStream_t st,
+                      int mode = 0, int h0 = 0, int hn = -1) {
     const int logP = log2_exact(c->page_size);
+    if (hn < 0) hn = c->num_kv_heads;
     int64_t row_off = 0;
     for (int r0 = 0; r0 < b->num_reqs; r0 += APPEND_MAX_REQS) {
         const int n = std::min(APPEND_MAX_REQS, b->num_reqs - r0);
@@ -172,6 +175,8 @@ ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k
         p.logP = logP;
         p.max_pages = b->max_pages_per_req;
         p.req0 = r0;
+        p.h0 = h0;
+        p.hn = hn;
         int max_touched = 0;
         for (int i = 0; i < n; ++i) {
             const int C = b->h_ctx_len[r0 + i], L = b->h_incr_len[r0 + i];
@@ -181,7 +186,10 @@ ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k
             row_off += L;
             if (L > 0) max_touched = std::max(max_touched, (C + L - 1) / c->page_size - C / c->page_size + 1);
         }
-        HIP_TRY(launch_append(p, c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16, max_touched, n, st));
+        if (mode == 0)
+            HIP_TRY(launch_append(p, c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16, max_touched, n, st));
+        else
+            HIP_TRY(launch_kv_move(p, mode == 2, max_touched, n, st));
     }
     return AMPD_OK;
 }
@@ -298,6 +306,29 @@ ampd_status ampd_kv_append(const ampd_kv_cache* cache, const ampd_batch* batch, 
     if (sumL == 0) return AMPD_OK;
     if (!k_new || !v_new) return AMPD_ERR_INVALID_ARG;
     return do_append(cache, batch, k_new, v_new, static_cast<hipStream_t>(stream));
+}
+
+static ampd_status kv_move(const ampd_kv_cache* cache, const ampd_batch* batch, int32_t head_begin, int32_t head_count,
+                           const void* k_rows, const void* v_rows, void* stream, int mode) {
+    ampd_status vs = validate(cache, batch, true);
+    if (vs != AMPD_OK) return vs;
+    if (cache->kv_dtype != AMPD_KV_BF16) return AMPD_ERR_UNSUPPORTED;
+    if (head_begin < 0 || head_count <= 0 || head_begin + head_count > cache->num_kv_heads) return AMPD_ERR_INVALID_ARG;
+    int64_t sumL = 0;
+    for (int r = 0; r < batch->num_reqs; ++r) sumL += batch->h_incr_len[r];
+    if (sumL == 0) return AMPD_OK;
+    if (!k_rows || !v_rows) return AMPD_ERR_INVALID_ARG;
+    return do_append(cache, batch, k_rows, v_rows, static_cast<hipStream_t>(stream), mode, head_begin, head_count);
+}
+
+ampd_status ampd_kv_pack(const ampd_kv_cache* cache, const ampd_batch* batch, int32_t head_begin, int32_t head_count,
+                         void* k_out, void* v_out, void* stream) {
+    return kv_move(cache, batch, head_begin, head_count, k_out, v_out, stream, 2);
+}
+
+ampd_status ampd_kv_unpack(const ampd_kv_cache* cache, const ampd_batch* batch, int32_t head_begin, int32_t head_count,
+                           const void* k_in, const void* v_in, void* stream) {
+    return kv_move(cache, batch, head_begin, head_count, k_in, v_in, stream, 1);
 }
 
 ampd_status ampd_incr_prefill_attn_opts(const ampd_kv_cache* cache, const ampd_batch* batch, const void* q,

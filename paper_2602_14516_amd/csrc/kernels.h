@@ -36,6 +36,7 @@ struct AppendParams {
     float* v_scale;
     const int32_t* block_table;
     int32_t Hkv, D, P, logP, max_pages, req0;
+    int32_t h0, hn;            // KV heads [h0, h0 + hn) of the pool; the packed rows hold hn heads
     int32_t C[APPEND_MAX_REQS], L[APPEND_MAX_REQS], row_off[APPEND_MAX_REQS];
 };
 
@@ -45,5 +46,7 @@ hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStrea
 // max_rows: the largest nq * heads among the split tiles (sizes the second grid dimension)
 hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);
+// bf16 only: pack = pages -> packed rows (k_new / v_new are written), otherwise packed rows -> pages
+hipError_t launch_kv_move(const AppendParams& p, bool pack, int max_pages_touched, int nreq, hipStream_t st);
 
 }  // namespace ampd

@@ -781,26 +781,32 @@ __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// KV append, bf16 cache: a bit-exact scatter.  grid = (pages touched, requests, 2 {K,V})
+// KV append / pack / unpack, bf16 cache: bit-exact copies.  grid = (pages touched, requests, 2 {K,V})
 
-__global__ __launch_bounds__(WG) void append_bf16_kernel(const AppendParams p) {
+// PACK = false: packed rows [tokens][hn][D] -> pages (append, or unpack of a received head share);
+// PACK = true:  pages -> packed rows (the send buffer of a KV transfer).
+template <bool PACK>
+__global__ __launch_bounds__(WG) void kv_move_bf16_kernel(const AppendParams p) {
     const int r = blockIdx.y;
     const int C = p.C[r], L = p.L[r];
     const int lp = (C >> p.logP) + blockIdx.x;               // logical page
     const int t0 = max(C, lp << p.logP), t1 = min(C + L, (lp + 1) << p.logP);
     if (t0 >= t1) return;
     const int page = p.block_table[(int64_t)(p.req0 + r) * p.max_pages + lp];
-    const int cpt = p.Hkv * p.D / 8;                         // 16-byte chunks per token
+    const int cpt = p.hn * p.D / 8;                          // 16-byte chunks per packed token row
     const int cph = p.D / 8;
-    const char* src = static_cast<const char*>(blockIdx.z ? p.v_new : p.k_new);
-    char* dst = static_cast<char*>(blockIdx.z ? p.v_pool : p.k_pool);
+    char* rows = static_cast<char*>(const_cast<void*>(blockIdx.z ? p.v_new : p.k_new));
+    char* pool = static_cast<char*>(blockIdx.z ? p.v_pool : p.k_pool);
     const int total = (t1 - t0) * cpt;
     for (int u = threadIdx.x; u < total; u += WG) {
         const int t = t0 + u / cpt, rem = u % cpt;
         const int h = rem / cph, ch = rem % cph;
-        const u32x4 v = *reinterpret_cast<const u32x4*>(src + (((int64_t)(p.row_off[r] + t - C) * p.Hkv + h) * p.D + ch * 8) * 2);
-        const int64_t e = ((((int64_t)page * p.Hkv + h) << p.logP) + (t & (p.P - 1))) * p.D + ch * 8;
-        *reinterpret_cast<u32x4*>(dst + e * 2) = v;
+        char* rp = rows + (((int64_t)(p.row_off[r] + t - C) * p.hn + h) * p.D + ch * 8) * 2;
+        char* pp = pool + (((((int64_t)page * p.Hkv + p.h0 + h) << p.logP) + (t & (p.P - 1))) * p.D + ch * 8) * 2;
+        if (PACK)
+            *reinterpret_cast<u32x4*>(rp) = *reinterpret_cast<const u32x4*>(pp);
+        else
+            *reinterpret_cast<u32x4*>(pp) = *reinterpret_cast<const u32x4*>(rp);
     }
 }
 
@@ -951,9 +957,18 @@ hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, 
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st) {
     if (nreq <= 0 || max_pages_touched <= 0) return hipSuccess;
     if (kvt == KV_BF16)
-        hipLaunchKernelGGL(append_bf16_kernel, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL(kv_move_bf16_kernel<false>, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
     else
         hipLaunchKernelGGL(append_fp8_kernel, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
+    return hipGetLastError();
+}
+
+hipError_t launch_kv_move(const AppendParams& p, bool pack, int max_pages_touched, int nreq, hipStream_t st) {
+    if (nreq <= 0 || max_pages_touched <= 0) return hipSuccess;
+    if (pack)
+        hipLaunchKernelGGL(kv_move_bf16_kernel<true>, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
+    else
+        hipLaunchKernelGGL(kv_move_bf16_kernel<false>, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
     return hipGetLastError();
 }
 
