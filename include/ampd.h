@@ -170,7 +170,7 @@ ampd_status ampd_paged_attn(const ampd_kv_cache *cache, const ampd_batch *batch,
 /* Description of the work list the planner builds for a batch (host only; for tests and
  * for the benchmark's roofline accounting).  Returns AMPD_OK or a validation error. */
 typedef struct {
-    int64_t num_items;          /* attention work items (= workgroups of the attention launch) */
+    int64_t num_items;          /* attention work items (= workgroups of the attention launch), null items included */
     int64_t num_wide_items;     /* prefill tiles: up to 256 query rows, 8 waves share K/V tiles */
     int64_t num_narrow_items;   /* decode-style items: <= 32 query rows, 8 waves split the keys */
     int64_t num_combine_items;  /* query tiles whose key range was split */
@@ -182,8 +182,10 @@ ampd_status ampd_plan_describe(const ampd_kv_cache *cache, const ampd_batch *bat
                                const ampd_plan_options *opts, ampd_plan_info *info);
 
 /* Copy the planner's attention items, in launch order, to a HOST array of 10 int32 per item:
- * {request, kind (0 wide, 1 narrow), kv_head, first_head_in_group, heads, first_token, tokens,
+ * {request, kind (0 wide, 1 narrow, 2 null), kv_head, first_head_in_group, heads, first_token, tokens,
  *  key_begin, key_end, partial_offset (-1: the item writes final output)};
+ * a null item (request -1) does no work: workgroup i runs on accelerator die i % 8, and null items keep
+ * the wide items that follow on the die whose L2 holds their K/V stream;
  * writes at most max_items items, returns the total number (or a negative ampd_status). */
 int64_t ampd_plan_items(const ampd_kv_cache *cache, const ampd_batch *batch,
                         const ampd_plan_options *opts, int32_t *h_items, int64_t max_items);

@@ -272,10 +272,36 @@ template <int D, bool MASK>
 __device__ __forceinline__ void tile64(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
                                        float c, int rel, int lane) {
     using G_ = Geo<D>;
+    constexpr int NKK = G_::NKK;
     f32x16 S0, S1;
     bf16x8 P0[2], P1[2];
-    qk32<D>(kl, Q, S0, lane);
-    qk32<D>(kl + G_::B32, Q, S1, lane);
+    {
+        // S^T of both 32-key halves with the K fragments of a whole half in flight ahead of the matrix
+        // instructions that use them: the reads of half 1 are issued one by one behind the products of half 0.
+        const int r = lane & 31, g = lane >> 5;
+        const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
+        u32x4 f0[NKK], f1[NKK];
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) f0[kk] = *LDS_PTR(const u32x4, ka + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32);
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            f1[kk] = *LDS_PTR(const u32x4, ka + G_::B32 + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32);
+        S0 = f32x16{0};
+        S1 = f32x16{0};
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0[kk]), Q[kk], S0, 0, 0, 0);
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk)
+            S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1[kk]), Q[kk], S1, 0, 0, 0);
+        __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);           // NKK LDS reads
+#pragma unroll
+        for (int kk = 0; kk < NKK; ++kk) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one matrix instruction
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // one LDS read
+        }
+        __builtin_amdgcn_sched_group_barrier(0x008, NKK, 0);
+    }
     if (MASK) {
         mask32(S0, rel);
         mask32(S1, rel - 32);
@@ -729,8 +755,9 @@ template <int D, int KVT>
 __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) char smem_raw[Geo<D>::SMEM];
     const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
-    const ItemCtx ic = load_item(p, blockIdx.x);
     const int kind = (p.items[blockIdx.x].heads >> 24) & 0xff;
+    if (kind == KIND_NULL) return;                         // a filler that keeps the following items on their XCD
+    const ItemCtx ic = load_item(p, blockIdx.x);
     if (kind == KIND_WIDE)
         wide_body<D, KVT>(p, ic, smem);
     else

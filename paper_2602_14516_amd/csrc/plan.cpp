@@ -10,6 +10,7 @@ namespace {
 constexpr int KV_TILE = 64;          // keys per LDS tile of a wide item; split points are multiples of it
 constexpr int MIN_NARROW_CHUNK = 256;
 constexpr int MIN_WIDE_CHUNK = 1024;
+constexpr int NUM_XCD = 8;            // accelerator dies; workgroup i is dispatched to die i % NUM_XCD
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
 inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -111,17 +112,143 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
         }
     }
 
-    // 4. launch order: longest first within each kind (stable, so the order is a function of the
-    //    lengths only).  In a mixed batch the two kinds are interleaved in proportion to their
-    //    total cost, so that at any time some CUs run compute-bound tiles while others stream
-    //    decode rows, instead of one phase after the other.
-    std::stable_sort(order.begin(), order.end(), [](const Cost& a, const Cost& b) { return a.cost > b.cost; });
+    // 4. launch order.  Workgroup i runs on XCD i % NUM_XCD, and each XCD has its own L2, so the position of
+    //    an item in the launch order decides which L2 its K/V stream passes through.  Wide items that read
+    //    the same stream (same request and KV head: the query tiles of one prefill chunk, which all start at
+    //    key 0 and advance at the same rate) are therefore queued on the same XCD, next to each other, so
+    //    that the stream is fetched from HBM once and the other tiles hit in L2:
+    //      a. streams are dealt to the XCDs longest-processing-time first (a stream that is a large part of
+    //         one XCD's share is first cut into pieces, tile by tile);
+    //      b. inside an XCD, streams run longest keys first, and tiles of a stream longest first, so the
+    //         last workgroups of the launch are the short ones;
+    //         (then single items move from the heaviest queue to the lightest until they are level);
+    //      c. the XCD queues are interleaved position by position; null items pad a queue that is shorter
+    //         than the others.
+    //    Narrow items stream their key range exactly once, so they only need balance: longest first.  In a
+    //    mixed batch the two kinds alternate in runs of NUM_XCD in proportion to their total cost, so that at
+    //    any time some CUs run compute-bound tiles while others stream decode rows.
+    //    Everything is stable and depends on the lengths only.
     std::vector<int32_t> wide_ix, narrow_ix;
     double wide_cost = 0, narrow_cost = 0;
-    for (const Cost& c : order) {
-        const bool is_wide = ((out.items[c.idx].heads >> 24) & 0xff) == KIND_WIDE;
-        (is_wide ? wide_ix : narrow_ix).push_back(c.idx);
-        (is_wide ? wide_cost : narrow_cost) += (double)c.cost;
+    {
+        std::vector<Cost> nar;
+        struct Stream { int64_t cost = 0; int64_t max_keys = 0; std::vector<Cost> items; };
+        std::vector<Stream> streams;
+        std::vector<int32_t> stream_of((size_t)num_reqs * s.Hkv, -1);
+        for (const Cost& c : order) {
+            const Item& it = out.items[c.idx];
+            if (((it.heads >> 24) & 0xff) != KIND_WIDE) {
+                nar.push_back(c);
+                narrow_cost += (double)c.cost;
+                continue;
+            }
+            wide_cost += (double)c.cost;
+            int32_t& sid = stream_of[(size_t)it.req * s.Hkv + (it.heads & 0xff)];
+            if (sid < 0) {
+                sid = (int32_t)streams.size();
+                streams.emplace_back();
+            }
+            Stream& st = streams[sid];
+            st.cost += c.cost;
+            st.max_keys = std::max<int64_t>(st.max_keys, it.kv_end);
+            st.items.push_back(c);
+        }
+        std::stable_sort(nar.begin(), nar.end(), [](const Cost& a, const Cost& b) { return a.cost > b.cost; });
+        for (const Cost& c : nar) narrow_ix.push_back(c.idx);
+
+        // a. pieces well below one XCD's share, dealt to the least loaded XCD, heaviest first
+        const int64_t share = std::max<int64_t>(1, ceil_div((int64_t)wide_cost, NUM_XCD));
+        std::vector<Stream> pieces;
+        for (Stream& st : streams) {
+            std::stable_sort(st.items.begin(), st.items.end(), [](const Cost& a, const Cost& b) { return a.cost > b.cost; });
+            // pieces of a quarter share let the dies mix long and short streams, but a piece keeps at least 8
+            // tiles so that a die still reuses what it fetched; a power of two, so that equal streams deal evenly
+            const int64_t want = std::max<int64_t>(1, std::min<int64_t>(ceil_div(4 * st.cost, share), (int64_t)st.items.size() / 8));
+            int np = 1;
+            while (2 * np <= want && np < NUM_XCD) np *= 2;
+            const size_t base = pieces.size();
+            pieces.resize(base + np);
+            for (size_t i = 0; i < st.items.size(); ++i) {         // deal the tiles round-robin: equal pieces
+                Stream& pc = pieces[base + i % np];
+                pc.items.push_back(st.items[i]);
+                pc.cost += st.items[i].cost;
+                pc.max_keys = st.max_keys;
+            }
+        }
+        std::vector<int32_t> by_cost(pieces.size());
+        for (size_t i = 0; i < pieces.size(); ++i) by_cost[i] = (int32_t)i;
+        std::stable_sort(by_cost.begin(), by_cost.end(), [&](int32_t a, int32_t b) { return pieces[a].cost > pieces[b].cost; });
+        std::vector<int32_t> bin_pieces[NUM_XCD];
+        int64_t bin_cost[NUM_XCD] = {0};
+        for (int32_t pi : by_cost) {
+            int best = 0;
+            for (int x = 1; x < NUM_XCD; ++x)
+                if (bin_cost[x] < bin_cost[best]) best = x;
+            bin_pieces[best].push_back(pi);
+            bin_cost[best] += pieces[pi].cost;
+        }
+        // b. queue of every XCD
+        std::vector<Cost> queue[NUM_XCD];
+        for (int x = 0; x < NUM_XCD; ++x) {
+            std::stable_sort(bin_pieces[x].begin(), bin_pieces[x].end(),
+                             [&](int32_t a, int32_t b) { return pieces[a].max_keys > pieces[b].max_keys; });
+            for (int32_t pi : bin_pieces[x])
+                for (const Cost& c : pieces[pi].items) queue[x].push_back(c);
+        }
+        //    level the queues: the heaviest queue hands its last (shortest) item to the lightest one while that
+        //    lowers the maximum.  The result is kept only if the launch gets shorter when every queue is
+        //    replayed on the CUs of one XCD, which also sees the granularity of a few long items per CU.
+        const int cus = std::max(1, opt.wg_slots / NUM_XCD);
+        std::vector<int64_t> cu_free;
+        auto finish_time = [&](const std::vector<Cost>& q) {
+            cu_free.assign(cus, 0);                                 // min-heap of the CUs' free times
+            auto later = [](int64_t a, int64_t b) { return a > b; };
+            int64_t last = 0;
+            for (const Cost& c : q) {
+                std::pop_heap(cu_free.begin(), cu_free.end(), later);
+                cu_free.back() += c.cost;
+                last = std::max(last, cu_free.back());
+                std::push_heap(cu_free.begin(), cu_free.end(), later);
+            }
+            return last;
+        };
+        auto launch_time = [&](const std::vector<Cost>* q) {
+            int64_t t = 0;
+            for (int x = 0; x < NUM_XCD; ++x) t = std::max(t, finish_time(q[x]));
+            return t;
+        };
+        {
+            std::vector<Cost> trial[NUM_XCD];
+            int64_t sum[NUM_XCD];
+            for (int x = 0; x < NUM_XCD; ++x) {
+                trial[x] = queue[x];
+                sum[x] = bin_cost[x];
+            }
+            bool moved = false;
+            for (size_t moves = 0; moves < out.items.size(); ++moves) {
+                int hi = 0, lo = 0;
+                for (int x = 1; x < NUM_XCD; ++x) {
+                    if (sum[x] > sum[hi]) hi = x;
+                    if (sum[x] < sum[lo]) lo = x;
+                }
+                if (trial[hi].empty()) break;
+                const Cost c = trial[hi].back();
+                if (sum[lo] + c.cost >= sum[hi]) break;
+                trial[hi].pop_back();
+                trial[lo].push_back(c);
+                sum[hi] -= c.cost;
+                sum[lo] += c.cost;
+                moved = true;
+            }
+            if (moved && launch_time(trial) < launch_time(queue))
+                for (int x = 0; x < NUM_XCD; ++x) queue[x].swap(trial[x]);
+        }
+        // c. interleave; -1 stands for a null item that pads a shorter queue
+        size_t longest = 0;
+        for (int x = 0; x < NUM_XCD; ++x) longest = std::max(longest, queue[x].size());
+        for (size_t j = 0; j < longest; ++j)
+            for (int x = 0; x < NUM_XCD; ++x) wide_ix.push_back(j < queue[x].size() ? queue[x][j].idx : -1);
+        while (!wide_ix.empty() && wide_ix.back() < 0) wide_ix.pop_back();
     }
     std::vector<Item> sorted;
     sorted.reserve(out.items.size());
@@ -133,11 +260,18 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
             if (iw >= wide_ix.size()) take_wide = false;
             else if (in >= narrow_ix.size()) take_wide = true;
             else take_wide = dw * narrow_cost <= dn * wide_cost;      // the kind that lags behind its share
-            const int32_t idx = take_wide ? wide_ix[iw++] : narrow_ix[in++];
-            const Item& it = out.items[idx];
-            const double keys = it.kv_end - it.kv_begin;
-            (take_wide ? dw : dn) += take_wide ? keys * 4 : keys;
-            sorted.push_back(it);
+            for (int k = 0; k < NUM_XCD; ++k) {
+                if (take_wide ? iw >= wide_ix.size() : in >= narrow_ix.size()) break;
+                const int32_t idx = take_wide ? wide_ix[iw++] : narrow_ix[in++];
+                if (idx < 0) {
+                    sorted.push_back(Item{-1, pack_heads(0, 0, 0, KIND_NULL), 0, 0, 0, 0, -1, 0});
+                    continue;
+                }
+                const Item& it = out.items[idx];
+                const double keys = it.kv_end - it.kv_begin;
+                (take_wide ? dw : dn) += take_wide ? keys * 4 : keys;
+                sorted.push_back(it);
+            }
         }
     }
     out.items.swap(sorted);

@@ -8,6 +8,9 @@
 //   * narrow items -- blocks of at most 32 query rows (decode rows, very short chunks)
 //                     whose 8 waves split the key range (bandwidth-bound work),
 // optionally cutting an item's key range into pieces (split-KV) that a combine pass merges.
+// Workgroup i of a launch runs on accelerator die (XCD) i % 8, each with its own L2, so the
+// launch order also decides which L2 a K/V stream passes through; null items (no work) pad the
+// per-die queues to equal length.
 // Everything is computed from logical positions, never from physical page ids, so results
 // are bitwise independent of where pages live in the pool.
 #pragma once
@@ -16,7 +19,7 @@
 
 namespace ampd {
 
-enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1 };
+enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1, KIND_NULL = 2 };
 
 constexpr int ATTN_WAVES = 8;      // waves of an attention workgroup (one workgroup per CU)
 
@@ -25,7 +28,7 @@ struct ReqInfo {          // 16 B, one per request, device-visible
 };
 
 struct Item {             // 32 B, one per attention workgroup, device-visible
-    int32_t req;
+    int32_t req;          // -1 for a null item
     int32_t heads;        // kvh | g0 << 8 | gn << 16 | kind << 24
     int32_t q0, nq;       // first new-token index and token count of this item
     int32_t kv_begin, kv_end;   // key range [begin, end) in logical positions

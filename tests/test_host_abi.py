@@ -69,6 +69,9 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
     G = Hq // Hkv
     ranges = {}
     for req, kind, kvh, g0, gn, q0, nq, kb, ke, po in items.tolist():
+        if kind == 2:                                  # null item: pads a die's queue, does no work
+            assert req == -1 and nq == 0 and po == -1
+            continue
         assert 0 < gn <= 32 and g0 + gn <= G and nq > 0 and kb < ke and kb % 64 == 0
         assert nq * gn <= (256 if kind == 0 else 32)
         for g in range(g0, g0 + gn):
@@ -115,8 +118,50 @@ def test_planner_kinds_and_split_policy():
     b = A.plan_items(c, C, L, mp)
     assert np.array_equal(a, b)
     keys = (a[:, 8] - a[:, 7]).astype(np.int64)
-    wide = a[:, 1] == 0
-    assert np.all(np.diff(keys[wide]) <= 0) and np.all(np.diff(keys[~wide]) <= 0)     # longest first within a kind
+    wide, narrow = a[:, 1] == 0, a[:, 1] == 1
+    assert np.all(np.diff(keys[narrow]) <= 0)          # decode items: longest first
     # the two kinds are interleaved: both appear in every quarter of the launch order
-    for part in np.array_split(wide, 4):
-        assert part.any() and (~part).any()
+    for part_w, part_n in zip(np.array_split(wide, 4), np.array_split(narrow, 4)):
+        assert part_w.any() and part_n.any()
+    check_xcd_queues(a, 0.98)
+
+
+def check_xcd_queues(a, min_balance):
+    """Workgroup i runs on die i % 8: the tiles of one K/V stream (request, KV head) share a die, next to each
+    other and longest first, and the dies carry equal wide work."""
+    die = np.arange(len(a)) % 8
+    wide = a[:, 1] == 0
+    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
+    stream = a[:, 0].astype(np.int64) * 256 + a[:, 2]
+    one_die = 0
+    for s in np.unique(stream[wide]):
+        m = np.nonzero(wide & (stream == s))[0]
+        dies = np.unique(die[m])
+        if len(dies) == 1:
+            one_die += 1
+            rises = int((np.diff(keys[m]) > 0).sum())      # a heavy stream is cut into up to 8 pieces
+            assert rises <= 7
+            if rises == 0:
+                # adjacent in the die's queue: no wide item of another stream between the first and the last tile
+                between = (die == dies[0]) & wide & (np.arange(len(a)) >= m[0]) & (np.arange(len(a)) <= m[-1])
+                assert np.all(stream[between] == s)
+    assert one_die >= 0.9 * len(np.unique(stream[wide]))
+    load = np.array([keys[wide & (die == x)].sum() for x in range(8)])
+    assert load.min() >= min_balance * load.max()
+
+
+def test_planner_spreads_few_streams_over_all_dies():
+    # 4 long requests with one KV head: 4 streams for 8 dies; each is cut in pieces and the dies still level out
+    c = shape_cache(8, 1, 128, 32)
+    C, L = W.config_lengths(4)
+    mp = int(((C.astype(int) + L + 31) // 32).max())
+    a = A.plan_items(c, C, L, mp)
+    die = np.arange(len(a)) % 8
+    wide = a[:, 1] == 0
+    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
+    load = np.array([keys[wide & (die == x)].sum() for x in range(8)])
+    assert load.min() >= 0.97 * load.max()
+    assert int((a[:, 1] == 2).sum()) < 0.1 * len(a)    # null items
+    for x in range(8):                                  # every die keeps at least 8 tiles of a stream it touches
+        reqs, counts = np.unique(a[wide & (die == x), 0], return_counts=True)
+        assert counts.min() >= 8
