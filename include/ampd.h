@@ -29,7 +29,8 @@
  *     one byte per element for AMPD_KV_FP8_E4M3).  Token t of request r lives in page
  *     block_table[r][t / P], slot t % P.
  *   - Scales (8-bit cache only): k_scale, v_scale  float[num_pages][Hkv]; stored value =
- *     decode(code) * scale; scales are powers of two (see ampd_kv_append).
+ *     decode(code) * scale; scales are powers of two (see ampd_kv_append), and the attention
+ *     kernels rely on it: they apply the exponent of a scale only.
  *   - Block table: int32 [num_reqs][max_pages_per_req], physical page ids.  Entries at
  *     index >= ceil(T_r / P) are never read (use -1).
  *   - Packed rows: q / out are bf16 [sum_r L_r][Hq][d], k_new / v_new bf16

@@ -109,22 +109,18 @@ struct RawChunk<KV_FP8> {
     static constexpr int ES = 1;
     __device__ __forceinline__ void zero() { v = u32x2{0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
-        v = *reinterpret_cast<const u32x2*>(base + lane_off);
+        v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + lane_off));
     }
-    // decode(code) * scale is exact in bf16: 4 significant bits times a power of two
+    // decode(code) * scale is exact in bf16: 4 significant bits times a power of two.  The page scales are
+    // powers of two (the append kernel writes no others), so the hardware's scaled conversion, which applies
+    // the exponent of `scale` only, is that product: one instruction per two elements.
     __device__ __forceinline__ u32x4 widen(float scale) const {
-        uint32_t w[2] = {v.x, v.y};
-        uint32_t o[4];
-#pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            f32x2 lo = __builtin_amdgcn_cvt_pk_f32_fp8(w[h], false);
-            f32x2 hi = __builtin_amdgcn_cvt_pk_f32_fp8(w[h], true);
-            bf16x2 a = {(__bf16)(lo.x * scale), (__bf16)(lo.y * scale)};
-            bf16x2 b = {(__bf16)(hi.x * scale), (__bf16)(hi.y * scale)};
-            o[2 * h] = __builtin_bit_cast(uint32_t, a);
-            o[2 * h + 1] = __builtin_bit_cast(uint32_t, b);
-        }
-        return u32x4{o[0], o[1], o[2], o[3]};
+        const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, scale, false);
+        const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, scale, true);
+        const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, scale, false);
+        const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, scale, true);
+        return u32x4{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, c),
+                     __builtin_bit_cast(uint32_t, d)};
     }
 };
 
@@ -782,21 +778,44 @@ __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
     constexpr int QPR = D / 4;                         // float4 groups per row
     for (int u = threadIdx.x; u < nr * QPR; u += WG) {
         const int r = r0 + u / QPR, dq = (u % QPR) * 4;
+        // The splits are walked four at a time, all loads of a group issued before any is used: with one
+        // load in flight per thread the kernel would pay one memory latency per split, twice.
+        constexpr int UN = 4;
+        const float* part0 = p.partial + ci.part_off;
+        const int64_t ml_off = (int64_t)rows * D + r * 2;
         float mall = NEG_INF;
-        for (int s = 0; s < ci.nsplit; ++s) {
-            const float* ml = p.partial + ci.part_off + (int64_t)s * ci.part_stride + (int64_t)rows * D + r * 2;
-            mall = fmaxf(mall, ml[0]);
+        for (int s0 = 0; s0 < ci.nsplit; s0 += UN) {
+            float mv[UN];
+#pragma unroll
+            for (int j = 0; j < UN; ++j) {
+                const int sp = min(s0 + j, ci.nsplit - 1);          // the tail re-reads the last split: max is idempotent
+                mv[j] = part0[(int64_t)sp * ci.part_stride + ml_off];
+            }
+#pragma unroll
+            for (int j = 0; j < UN; ++j) mall = fmaxf(mall, mv[j]);
         }
         const float muse = mall == NEG_INF ? 0.0f : mall;
         float lsum = 0.0f;
         f32x4 acc = {0, 0, 0, 0};
-        for (int s = 0; s < ci.nsplit; ++s) {
-            const float* base = p.partial + ci.part_off + (int64_t)s * ci.part_stride;
-            const float* ml = base + (int64_t)rows * D + r * 2;
-            const float w = fast_exp2(ml[0] - muse);
-            lsum += ml[1] * w;
-            const f32x4 o = *reinterpret_cast<const f32x4*>(base + (int64_t)r * D + dq);
-            acc += o * w;
+        for (int s0 = 0; s0 < ci.nsplit; s0 += UN) {
+            float mv[UN], lv[UN];
+            f32x4 ov[UN];
+#pragma unroll
+            for (int j = 0; j < UN; ++j) {
+                const int sp = min(s0 + j, ci.nsplit - 1);
+                const float* base = part0 + (int64_t)sp * ci.part_stride;
+                mv[j] = base[ml_off];
+                lv[j] = base[ml_off + 1];
+                ov[j] = *reinterpret_cast<const f32x4*>(base + (int64_t)r * D + dq);
+            }
+#pragma unroll
+            for (int j = 0; j < UN; ++j) {
+                if (s0 + j < ci.nsplit) {                            // (the tail's duplicate loads are dropped)
+                    const float w = fast_exp2(mv[j] - muse);
+                    lsum += lv[j] * w;
+                    acc += ov[j] * w;
+                }
+            }
         }
         const float inv = 1.0f / lsum;
         const int tl = r / gn, hg = r - tl * gn;
@@ -837,8 +856,9 @@ __global__ __launch_bounds__(WG) void kv_move_bf16_kernel(const AppendParams p) 
     }
 }
 
-// KV append, 8-bit cache.  grid = (pages touched, requests, 2 {K,V}); the block walks the KV
-// heads; per head: amax of the new tokens -> exponent -> (re-encode old slots) -> encode.
+// KV append, 8-bit cache.  grid = (pages touched, requests, 2 {K,V} x KV heads): one block per
+// (page, head), so that the chain amax of the new tokens -> exponent -> (re-encode old slots) -> encode,
+// which is a few dependent memory round trips, runs for all heads at once.
 __device__ __forceinline__ int exponent_for(float amax) {
     // smallest e with amax <= 448 * 2^e  (448 = 1.75 * 2^8), clamped to [-40, 119]
     const uint32_t u = __float_as_uint(amax);
@@ -865,12 +885,13 @@ __global__ __launch_bounds__(WG) void append_fp8_kernel(const AppendParams p) {
     if (t0 >= t1) return;
     const int page = p.block_table[(int64_t)(p.req0 + r) * p.max_pages + lp];
     const int n_old = max(0, C - (lp << p.logP));
-    const char* src = static_cast<const char*>(blockIdx.z ? p.v_new : p.k_new);
-    uint8_t* dst = static_cast<uint8_t*>(blockIdx.z ? p.v_pool : p.k_pool);
-    float* scl = blockIdx.z ? p.v_scale : p.k_scale;
+    const int is_v = blockIdx.z & 1, h = blockIdx.z >> 1;
+    const char* src = static_cast<const char*>(is_v ? p.v_new : p.k_new);
+    uint8_t* dst = static_cast<uint8_t*>(is_v ? p.v_pool : p.k_pool);
+    float* scl = is_v ? p.v_scale : p.k_scale;
     const int cph = p.D / 8;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    for (int h = 0; h < p.Hkv; ++h) {
+    {
         // 1. amax over the new tokens of this (page, head)
         float amax = 0.0f;
         const int total = (t1 - t0) * cph;
@@ -934,7 +955,6 @@ __global__ __launch_bounds__(WG) void append_fp8_kernel(const AppendParams p) {
             o.y = encode4(f[4], f[5], f[6], f[7]);
             *reinterpret_cast<u32x2*>(pg + (int64_t)(t & (p.P - 1)) * p.D + ch * 8) = o;
         }
-        __syncthreads();                                       // red / e_sh are reused by the next head
     }
 }
 
@@ -986,7 +1006,7 @@ hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, 
     if (kvt == KV_BF16)
         hipLaunchKernelGGL(kv_move_bf16_kernel<false>, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
     else
-        hipLaunchKernelGGL(append_fp8_kernel, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL(append_fp8_kernel, dim3(max_pages_touched, nreq, 2 * p.Hkv), dim3(WG), 0, st, p);
     return hipGetLastError();
 }
 

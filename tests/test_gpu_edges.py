@@ -39,6 +39,22 @@ def test_head_group_shapes(name, C, L, Hq, Hkv, d, P):
         assert np.array_equal(out.reshape(2, Hq, d), np.repeat(b.v_new, G, axis=1))
 
 
+@pytest.mark.parametrize("C,L,Hq,Hkv", [
+    ([1211], [338], 16, 2),                          # 2 K/V streams for 8 dies: pieces, levelling, null items
+    ([1355, 407, 542], [618, 147, 63], 8, 1),        # 3 streams of very different weight
+    ([1325, 1308, 459, 27], [549, 501, 544, 20], 8, 1),
+])
+def test_launch_order_with_null_items(C, L, Hq, Hkv):
+    """Few K/V streams: the per-die queues differ in length and are padded with null items, which must do nothing."""
+    print(f"case: null items C={C} L={L}", flush=True)
+    b = W.make_batch(C, L, Hq, Hkv, 128, 16, seed=sum(C) + Hq, poison=True)
+    db = DevBatch(b)
+    items = A.plan_items(db.cache, b.ctx_len, b.incr_len, b.block_table.shape[1])
+    assert (items[:, 1] == 2).any(), "this case is meant to produce null items"
+    out = run(db)
+    compare(b, out, rows=sample_rows(b, 12, seed=2), label="null items")
+
+
 def test_more_requests_than_one_append_launch_carries():
     print("case: 300 decode rows + 3 prefill rows", flush=True)
     rng = np.random.default_rng(3)
