@@ -152,9 +152,17 @@ ampd_status ensure_timing_events() {
 
 // ---- launches --------------------------------------------------------------------------------
 
-// mode 0: append (all heads);  1: unpack rows of heads [h0, h0+hn) into pages;  2: pack pages into rows
+// A work list staged in pinned host memory that still has to reach the workspace.
+struct PendingUpload {
+    const void* src = nullptr;
+    void* dst = nullptr;
+    size_t bytes = 0;
+};
+
+// mode 0: append (all heads);  1: unpack rows of heads [h0, h0+hn) into pages;  2: pack pages into rows.
+// up (mode 0 only): rides on the first launch that is actually made; bytes is set to 0 once it is on its way.
 ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k_new, const void* v_new, hipStream_t st,
-                      int mode = 0, int h0 = 0, int hn = -1) {
+                      int mode = 0, int h0 = 0, int hn = -1, PendingUpload* up = nullptr) {
     const int logP = log2_exact(c->page_size);
     if (hn < 0) hn = c->num_kv_heads;
     int64_t row_off = 0;
@@ -186,9 +194,15 @@ ampd_status do_append(const ampd_kv_cache* c, const ampd_batch* b, const void* k
             row_off += L;
             if (L > 0) max_touched = std::max(max_touched, (C + L - 1) / c->page_size - C / c->page_size + 1);
         }
-        if (mode == 0)
+        if (mode == 0) {
+            if (up && up->bytes > 0 && max_touched > 0) {
+                p.up_src = up->src;
+                p.up_dst = up->dst;
+                p.up_n16 = (int32_t)((up->bytes + 15) / 16);
+                up->bytes = 0;
+            }
             HIP_TRY(launch_append(p, c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16, max_touched, n, st));
-        else
+        } else
             HIP_TRY(launch_kv_move(p, mode == 2, max_touched, n, st));
     }
     return AMPD_OK;
@@ -200,20 +214,36 @@ ampd_status check_workspace(const Plan& plan, const void* workspace, size_t work
     return AMPD_OK;
 }
 
-// plan: already built and checked against the workspace
+// Stage the work list in a pinned ring slot (the caller holds g_mu and, once the launch that reads the slot
+// is enqueued, records the slot's event and marks it pending).
+ampd_status stage_plan(const Plan& plan, void* workspace, Slot** slot, PendingUpload* up) {
+    HIP_TRY(take_slot((size_t)plan.plan_bytes, slot));
+    char* h = static_cast<char*>((*slot)->host);
+    std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
+    std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(Item));
+    if (!plan.combs.empty()) std::memcpy(h + plan.off_combs, plan.combs.data(), plan.combs.size() * sizeof(CombItem));
+    up->src = h;
+    up->dst = workspace;
+    up->bytes = (size_t)plan.plan_bytes;
+    return AMPD_OK;
+}
+
+// plan: already built and checked against the workspace.  append: the K/V rows to append first (or null).
 ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& plan, const void* q, void* out,
-                    void* workspace, hipStream_t st) {
-    if (plan.items.empty()) return AMPD_OK;
+                    void* workspace, hipStream_t st, const void* k_new = nullptr, const void* v_new = nullptr) {
+    if (plan.items.empty()) return k_new ? do_append(c, b, k_new, v_new, st) : AMPD_OK;
 
     {
         std::lock_guard<std::mutex> lk(g_mu);
         Slot* s = nullptr;
-        HIP_TRY(take_slot((size_t)plan.plan_bytes, &s));
-        char* h = static_cast<char*>(s->host);
-        std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
-        std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(Item));
-        if (!plan.combs.empty()) std::memcpy(h + plan.off_combs, plan.combs.data(), plan.combs.size() * sizeof(CombItem));
-        HIP_TRY(launch_upload(h, workspace, (size_t)plan.plan_bytes, st));
+        PendingUpload up;
+        ampd_status vs = stage_plan(plan, workspace, &s, &up);
+        if (vs != AMPD_OK) return vs;
+        if (k_new) {
+            vs = do_append(c, b, k_new, v_new, st, 0, 0, -1, &up);     // the work list rides on the append launch
+            if (vs != AMPD_OK) return vs;
+        }
+        if (up.bytes > 0) HIP_TRY(launch_upload(up.src, up.dst, up.bytes, st));
         HIP_TRY(hipEventRecord(s->ev, st));
         s->pending = true;
     }
@@ -277,9 +307,7 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
         HIP_TRY(hipEventRecord(t_ev[0], st));
         t_has_append = true;
     }
-    vs = do_append(c, b, k_new, v_new, st);
-    if (vs != AMPD_OK) return vs;
-    return do_attn(c, b, plan, q, out, workspace, st);
+    return do_attn(c, b, plan, q, out, workspace, st, k_new, v_new);
 }
 
 }  // namespace

@@ -37,6 +37,11 @@ struct AppendParams {
     const int32_t* block_table;
     int32_t Hkv, D, P, logP, max_pages, req0;
     int32_t h0, hn;            // KV heads [h0, h0 + hn) of the pool; the packed rows hold hn heads
+    // Optional rider: the work list of the attention launch that follows, copied from pinned host memory
+    // into the workspace by one extra z-slice of this launch (up_n16 16-byte vectors; 0: none).
+    const void* up_src;
+    void* up_dst;
+    int32_t up_n16;
     int32_t C[APPEND_MAX_REQS], L[APPEND_MAX_REQS], row_off[APPEND_MAX_REQS];
 };
 

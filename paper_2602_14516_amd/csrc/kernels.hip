@@ -829,10 +829,23 @@ __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
 // ---------------------------------------------------------------------------------------------
 // KV append / pack / unpack, bf16 cache: bit-exact copies.  grid = (pages touched, requests, 2 {K,V})
 
+// The z-slice past the K / V slices of an append launch carries the work list of the attention launch
+// that follows from pinned host memory into the workspace (saves a launch per call).
+__device__ __forceinline__ void upload_rider(const AppendParams& p) {
+    const u32x4* src = static_cast<const u32x4*>(p.up_src);
+    u32x4* dst = static_cast<u32x4*>(p.up_dst);
+    const int nthreads = gridDim.x * gridDim.y * WG;
+    for (int i = (blockIdx.y * gridDim.x + blockIdx.x) * WG + threadIdx.x; i < p.up_n16; i += nthreads) dst[i] = src[i];
+}
+
 // PACK = false: packed rows [tokens][hn][D] -> pages (append, or unpack of a received head share);
 // PACK = true:  pages -> packed rows (the send buffer of a KV transfer).
 template <bool PACK>
 __global__ __launch_bounds__(WG) void kv_move_bf16_kernel(const AppendParams p) {
+    if (blockIdx.z == 2) {
+        upload_rider(p);
+        return;
+    }
     const int r = blockIdx.y;
     const int C = p.C[r], L = p.L[r];
     const int lp = (C >> p.logP) + blockIdx.x;               // logical page
@@ -878,6 +891,10 @@ __device__ __forceinline__ uint32_t encode4(float a, float b, float c, float d) 
 __global__ __launch_bounds__(WG) void append_fp8_kernel(const AppendParams p) {
     __shared__ float red[WG / 64];
     __shared__ int e_sh[2];
+    if ((int)blockIdx.z == 2 * p.Hkv) {
+        upload_rider(p);
+        return;
+    }
     const int r = blockIdx.y;
     const int C = p.C[r], L = p.L[r];
     const int lp = (C >> p.logP) + blockIdx.x;
@@ -1002,11 +1019,12 @@ hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, 
 }
 
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st) {
-    if (nreq <= 0 || max_pages_touched <= 0) return hipSuccess;
+    if (nreq <= 0 || max_pages_touched <= 0) return hipSuccess;               // (the caller keeps a rider for later)
+    const int rider = p.up_n16 > 0 ? 1 : 0;
     if (kvt == KV_BF16)
-        hipLaunchKernelGGL(kv_move_bf16_kernel<false>, dim3(max_pages_touched, nreq, 2), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL(kv_move_bf16_kernel<false>, dim3(max_pages_touched, nreq, 2 + rider), dim3(WG), 0, st, p);
     else
-        hipLaunchKernelGGL(append_fp8_kernel, dim3(max_pages_touched, nreq, 2 * p.Hkv), dim3(WG), 0, st, p);
+        hipLaunchKernelGGL(append_fp8_kernel, dim3(max_pages_touched, nreq, 2 * p.Hkv + rider), dim3(WG), 0, st, p);
     return hipGetLastError();
 }
 

@@ -9,6 +9,7 @@ namespace {
 
 constexpr int KV_TILE = 64;          // keys per LDS tile of a wide item; split points are multiples of it
 constexpr int MIN_NARROW_CHUNK = 256;
+constexpr int NARROW_FAT_CHUNK = 4096;
 constexpr int MIN_WIDE_CHUNK = 1024;
 constexpr int NUM_XCD = 8;            // accelerator dies; workgroup i is dispatched to die i % NUM_XCD
 
@@ -65,8 +66,12 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
     int64_t narrow_chunk = 1 << 30, wide_chunk = 1 << 30;
     if (opt.force_kv_splits <= 0) {
         if (narrow_keys > 0) {
-            // aim at ~8 items per resident workgroup slot so that the tail is short
-            narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(ceil_div(narrow_keys, 8 * (int64_t)opt.wg_slots), KV_TILE));
+            // ~8 items per resident workgroup slot keep the tail short, but an item costs a few microseconds
+            // before its first key arrives (item, Q, page ids, first block), about as long as streaming 100 KB:
+            // small launches therefore take chunks of up to NARROW_FAT_CHUNK keys as long as ~2 items per slot remain
+            const int64_t fine = ceil_div(narrow_keys, 8 * (int64_t)opt.wg_slots);
+            const int64_t coarse = ceil_div(narrow_keys, 2 * (int64_t)opt.wg_slots);
+            narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(std::min(coarse, std::max<int64_t>(NARROW_FAT_CHUNK, fine)), KV_TILE));
         }
         if (n_wide > 0 && n_wide < 2 * (int64_t)opt.wg_slots) {
             int64_t max_keys = 0;
