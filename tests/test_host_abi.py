@@ -165,3 +165,31 @@ def test_planner_spreads_few_streams_over_all_dies():
     for x in range(8):                                  # every die keeps at least 8 tiles of a stream it touches
         reqs, counts = np.unique(a[wide & (die == x), 0], return_counts=True)
         assert counts.min() >= 8
+
+
+def test_narrow_chunk_policy_small_and_large_launches():
+    """Decode rows: ~8 items per CU in a large launch; a small launch takes fatter chunks (an item costs a few
+    microseconds before its first key arrives) but keeps about two items per CU."""
+    c = shape_cache(32, 8, 128, 16)
+    # a 32-row decode tick over 6000-token contexts: 1.5 M keys
+    C = np.full(32, 6000, np.int32)
+    L = np.ones(32, np.int32)
+    a = A.plan_items(c, C, L, 6001 // 16 + 1)
+    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
+    assert np.all(a[:, 1] == 1)
+    assert 2 * 256 <= len(a) <= 3 * 256 and keys.max() <= 4096 and keys.max() % 64 == 0
+    # the decode rows of configuration 3: 7 M keys; keys / (8 x 256) = 3.5 k is below the 4096 of a small launch
+    c3 = shape_cache(64, 8, 128, 16)
+    C3, L3 = W.config_lengths(3, part="decode")
+    a3 = A.plan_items(c3, C3, L3, int(((C3.astype(int) + L3 + 15) // 16).max()))
+    k3 = (a3[:, 8] - a3[:, 7]).astype(np.int64)
+    assert k3.max() == 4096 and 7 * 256 <= len(a3) <= 11 * 256
+    # twice the rows: the ~8-items-per-CU rule takes over
+    a6 = A.plan_items(c3, np.concatenate([C3, C3]), np.concatenate([L3, L3]), int(((C3.astype(int) + L3 + 15) // 16).max()))
+    k6 = (a6[:, 8] - a6[:, 7]).astype(np.int64)
+    total = 2 * int((C3.astype(np.int64) + 1).sum()) * 8
+    assert k6.max() == -(-(-(-total // 2048)) // 64) * 64 and k6.max() > 4096
+    # a tiny launch never goes below 256-key chunks
+    a1 = A.plan_items(c, np.full(4, 700, np.int32), np.ones(4, np.int32), 701 // 16 + 1)
+    k1 = (a1[:, 8] - a1[:, 7]).astype(np.int64)
+    assert k1.max() == 256 and len(a1) == 4 * 8 * 3
