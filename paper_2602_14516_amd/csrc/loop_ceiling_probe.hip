@@ -1,0 +1,202 @@
+// Ceiling probe for the wide attention loop on gfx950 (measurement aid, not part of the library).
+//
+// What does the instruction mix of the prefill-tile loop reach on this device when everything that is
+// specific to the real kernel (paged addressing, masks, ragged tiles, work-list scheduling) is taken away?
+// Three kernels, all with 8 waves x 32 query rows per workgroup and one workgroup per CU:
+//   mfma_only   back-to-back v_mfma_f32_32x32x16_bf16 on register operands: the matrix peak and the clock;
+//   attn_loop   per 64 keys and wave: S^T = K Q^T (16 products, K fragments read from LDS), row max, 32 x
+//               (fma, exp2, add, convert), O^T += V^T P^T (16 products, V fragments by transposing LDS reads),
+//               one workgroup barrier per 128 keys -- with or without the direct global -> LDS loads of the next
+//               128-key stage (64 KB per workgroup, from a buffer that stays in L2 or from one that does not).
+// Every address is in bounds by construction, every loop has a fixed trip count, nothing is checked
+// numerically: only the time matters.  Prints one JSON line.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdio>
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+#define LDS_PTR(T, a) ((__attribute__((address_space(3))) T*)(uintptr_t)(a))
+
+__device__ unsigned long long g_clk[2];          // shader cycles and 100 MHz ticks of workgroup 0, wave 0
+
+__global__ __launch_bounds__(512, 1) void mfma_only(float* out, int iters) {
+    bf16x8 a, b;
+    for (int i = 0; i < 8; ++i) {
+        a[i] = (__bf16)(0.25f * (float)((threadIdx.x + i) & 3));
+        b[i] = (__bf16)(0.5f + 0.125f * (float)(i & 1));
+    }
+    f32x16 acc[2] = {f32x16{0}, f32x16{0}};
+    const uint64_t c0 = __builtin_readcyclecounter(), w0 = __builtin_amdgcn_s_memrealtime();
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc[1], 0, 0, 0);
+        }
+    }
+    const uint64_t c1 = __builtin_readcyclecounter(), w1 = __builtin_amdgcn_s_memrealtime();
+    float s = 0;
+    for (int i = 0; i < 16; ++i) s += acc[0][i] + acc[1][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        g_clk[0] = c1 - c0;
+        g_clk[1] = w1 - w0;
+    }
+}
+
+__device__ __forceinline__ void direct_load16(const char* gbase, uint32_t voff, uint32_t lds) {
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase) : "memory");
+}
+
+// LOADS: 0 none, 1 the next stage's 64 KB by direct loads (8 per wave), issued at the start of the stage.
+// src: per-workgroup region of `span` bytes (a power of two >= 64 KB), walked stage by stage.
+template <int LOADS>
+__global__ __launch_bounds__(512, 1) void attn_loop(float* out, const char* src, uint32_t span, int stages, float c) {
+    extern __shared__ __attribute__((aligned(16))) char smem_dyn[];
+    const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_dyn);
+    for (int i = threadIdx.x; i < 32768; i += 512) ((uint32_t*)smem_dyn)[i] = 0x3c003c00u + (uint32_t)(i & 7);
+    __syncthreads();
+    const int lane = threadIdx.x & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    bf16x8 Q[8];
+    for (int k = 0; k < 8; ++k)
+        for (int i = 0; i < 8; ++i) Q[k][i] = (__bf16)(0.01f * (float)((lane + k + i) & 7));
+    f32x16 O[4] = {f32x16{0}, f32x16{0}, f32x16{0}, f32x16{0}};
+    float m = 0.f, l = 0.f;
+    const char* wg_src = src + (size_t)blockIdx.x * span;
+    const uint64_t c0 = __builtin_readcyclecounter(), w0 = __builtin_amdgcn_s_memrealtime();
+    for (int t = 0; t < stages; ++t) {
+        // stage = 128 keys: K at +0 (2 units x 16 KB), V at +32 KB; two stages of 64 KB
+        const uint32_t cur = smem + (t & 1) * 65536, nxt = smem + ((t + 1) & 1) * 65536;
+        if (LOADS) {
+            const uint32_t goff = __builtin_amdgcn_readfirstlane(((uint32_t)(t + 1) * 65536u) & (span - 1));
+            const char* gsrc = wg_src + goff + wv * 8192;           // this wave's 8 KB of the next stage
+#pragma unroll
+            for (int g = 0; g < 8; ++g)
+                direct_load16(gsrc + g * 1024, lane * 16, __builtin_amdgcn_readfirstlane(nxt + wv * 8192 + g * 1024));
+        }
+#pragma unroll
+        for (int u = 0; u < 2; ++u) {
+            const uint32_t base = cur + u * 16384;
+            f32x16 S[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                S[h] = f32x16{0};
+#pragma unroll
+                for (int kk = 0; kk < 8; ++kk) {
+                    const bf16x8 a = __builtin_bit_cast(bf16x8, *LDS_PTR(const u32x4, base + h * 8192 + kk * 1024 + lane * 16));
+                    S[h] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, Q[kk], S[h], 0, 0, 0);
+                }
+            }
+            float mx = S[0][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, S[0][i]);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) mx = fmaxf(mx, S[1][i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32));
+            m = fmaxf(m, mx * c);
+            bf16x8 P[2][2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float pv = __builtin_amdgcn_exp2f(__builtin_fmaf(S[h][i], c, -m));
+                    l += pv;
+                    P[h][i >> 3][i & 7] = (__bf16)pv;
+                }
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+                for (int cc = 0; cc < 2; ++cc)
+#pragma unroll
+                    for (int db = 0; db < 4; ++db) {
+                        const uint32_t a0 = base + 32768 + h * 8192 + cc * 4096 + db * 1024 + lane * 8;
+                        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+                        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + 512));
+                        const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        O[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, av), P[h][cc], O[db], 0, 0, 0);
+                    }
+        }
+        if (LOADS) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+    }
+    const uint64_t c1 = __builtin_readcyclecounter(), w1 = __builtin_amdgcn_s_memrealtime();
+    float s = l + m;
+    for (int k = 0; k < 4; ++k)
+        for (int i = 0; i < 16; ++i) s += O[k][i];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        g_clk[0] = c1 - c0;
+        g_clk[1] = w1 - w0;
+    }
+}
+
+#define CK(x)                                                                        \
+    do {                                                                             \
+        hipError_t e_ = (x);                                                         \
+        if (e_ != hipSuccess) {                                                      \
+            fprintf(stderr, "%s: %s (line %d)\n", #x, hipGetErrorString(e_), __LINE__); \
+            return 1;                                                                \
+        }                                                                            \
+    } while (0)
+
+struct Result {
+    double ms, ghz;
+};
+
+template <class F>
+static int measure(F&& launch, int warm, int reps, Result* r) {
+    hipEvent_t e0, e1;
+    CK(hipEventCreate(&e0));
+    CK(hipEventCreate(&e1));
+    for (int i = 0; i < warm; ++i) launch();
+    CK(hipDeviceSynchronize());
+    CK(hipEventRecord(e0));
+    for (int i = 0; i < reps; ++i) launch();
+    CK(hipEventRecord(e1));
+    CK(hipEventSynchronize(e1));
+    float ms = 0;
+    CK(hipEventElapsedTime(&ms, e0, e1));
+    unsigned long long clk[2];
+    CK(hipMemcpyFromSymbol(clk, HIP_SYMBOL(g_clk), sizeof(clk)));
+    r->ms = ms / reps;
+    r->ghz = clk[1] ? (double)clk[0] / (double)clk[1] * 0.1 : 0.0;
+    CK(hipGetLastError());
+    return 0;
+}
+
+int main() {
+    const int NWG = 512;                               // two workgroups per CU, one after the other
+    const int STAGES = 1000;                           // 128-key stages per workgroup
+    float* out;
+    char* src;
+    const size_t span_big = 4u << 20;                  // 4 MB per workgroup: 2 GB in total, streams from HBM
+    CK(hipMalloc(&out, (size_t)NWG * 512 * sizeof(float)));
+    CK(hipMalloc(&src, (size_t)NWG * span_big));
+    CK(hipMemset(src, 0x3c, (size_t)NWG * span_big));
+    CK(hipFuncSetAttribute((const void*)attn_loop<0>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    CK(hipFuncSetAttribute((const void*)attn_loop<1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+
+    // 64 products of 32x32x16 per wave and stage, 8 waves
+    const double flop_stage = 8.0 * 64.0 * 32768.0;
+    Result r_mfma, r_loop, r_l2, r_hbm;
+    const int MF_ITERS = 4000;                         // x 16 products
+    if (measure([&] { hipLaunchKernelGGL(mfma_only, dim3(NWG), dim3(512), 0, 0, out, MF_ITERS); }, 20, 20, &r_mfma)) return 1;
+    if (measure([&] { hipLaunchKernelGGL(attn_loop<0>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_loop)) return 1;
+    if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_l2)) return 1;
+    if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, (uint32_t)span_big, STAGES, 0.1f); }, 20, 20, &r_hbm)) return 1;
+    const double tf_mfma = (double)NWG * 8 * MF_ITERS * 16 * 32768.0 / (r_mfma.ms * 1e-3) / 1e12;
+    auto tf = [&](const Result& r) { return (double)NWG * STAGES * flop_stage / (r.ms * 1e-3) / 1e12; };
+    auto tbs = [&](const Result& r) { return (double)NWG * STAGES * 65536.0 / (r.ms * 1e-3) / 1e12; };
+    printf("{\"mfma_only\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
+           "\"attn_loop_no_loads\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
+           "\"attn_loop_direct_loads_L2\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f, \"load_TBps\": %.2f}, "
+           "\"attn_loop_direct_loads_HBM\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f, \"load_TBps\": %.2f}}\n",
+           tf_mfma, r_mfma.ghz, tf(r_loop), r_loop.ghz, tf(r_l2), r_l2.ghz, tbs(r_l2), tf(r_hbm), r_hbm.ghz, tbs(r_hbm));
+    return 0;
+}
