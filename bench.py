@@ -313,7 +313,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'ceiling' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'ceiling' | 'simulate' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -331,6 +331,21 @@ def main():
         res = subprocess.run([PROBE], stdout=subprocess.PIPE, text=True, timeout=120)
         print(json.dumps({"only": "ceiling", **json.loads(res.stdout.strip().splitlines()[-1])}))
         sys.exit(res.returncode)
+
+    if args.only == "simulate":
+        # host only: the serving simulator on the fitted cost model, three routing policies x reordering on / off
+        from paper_2602_14516_amd import simulator as S
+        model = S.CostModel(**S.MI355X_ATTENTION)
+        sess = S.make_sessions(1, num_sessions=256, rounds=8, median=2048, tool_delay_mean=0.02, arrival_span=0.2,
+                               dec_lo=16, dec_hi=64)
+        outp = {"only": "simulate", "scenario": "256 sessions x 8 rounds, l_incr ~ lognormal(median 2048), 16-64 decode tokens per round, "
+                "1 prefill worker + 4 decode workers, 32 attention layers, TTFT <= 30 ms, ITL <= 12 ms"}
+        for pol in ("remote", "local", "adaptive"):
+            for w in (0, 5):
+                r = S.simulate(sess, model, n_prefill=1, n_decode=4, policy=pol, reorder_window=w, ttft_thres=0.03, itl_thres=0.012)
+                outp[f"{pol}{'+reorder' if w else ''}"] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in r.summary().items()}
+        print(json.dumps(outp))
+        return
 
     import torch
     import paper_2602_14516_amd as A
