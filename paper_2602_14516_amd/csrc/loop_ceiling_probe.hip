@@ -2,8 +2,10 @@
 //
 // What does the instruction mix of the prefill-tile loop reach on this device when everything that is
 // specific to the real kernel (paged addressing, masks, ragged tiles, work-list scheduling) is taken away?
-// Three kernels, all with 8 waves x 32 query rows per workgroup and one workgroup per CU:
+// Four kernels, all with 8 waves x 32 query rows per workgroup and one workgroup per CU:
 //   mfma_only   back-to-back v_mfma_f32_32x32x16_bf16 on register operands: the matrix peak and the clock;
+//   coexec      waves 0-3 (one per SIMD) run products only, waves 4-7 the vector work of the softmax only, each
+//               group alone and both together: how much of the vector work hides under the other wave's products;
 //   attn_loop   per 64 keys and wave: S^T = K Q^T (16 products, K fragments read from LDS), row max, 32 x
 //               (fma, exp2, add, convert), O^T += V^T P^T (16 products, V fragments by transposing LDS reads),
 //               one workgroup barrier per 128 keys -- with or without the direct global -> LDS loads of the next
@@ -47,6 +49,54 @@ __global__ __launch_bounds__(512, 1) void mfma_only(float* out, int iters) {
         g_clk[0] = c1 - c0;
         g_clk[1] = w1 - w0;
     }
+}
+
+// WHO: 1 = waves 0-3 issue 32 products per iteration, 2 = waves 4-7 do the vector work of one 64-key unit per
+// iteration (32 logits: max, fma, exp2, add, convert), 3 = both at once.  The groups share no data.
+template <int WHO>
+__global__ __launch_bounds__(512, 1) void coexec(float* out, int iters, float c) {
+    const int wave = threadIdx.x >> 6;
+    float s = 0;
+    if ((WHO & 1) && wave < 4) {
+        bf16x8 a, b;
+        for (int i = 0; i < 8; ++i) {
+            a[i] = (__bf16)(0.25f * (float)((threadIdx.x + i) & 3));
+            b[i] = (__bf16)(0.5f + 0.125f * (float)(i & 1));
+        }
+        f32x16 acc0 = f32x16{0}, acc1 = f32x16{0};
+        for (int it = 0; it < iters; ++it) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, acc0, 0, 0, 0);
+                acc1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b, a, acc1, 0, 0, 0);
+            }
+        }
+        for (int i = 0; i < 16; ++i) s += acc0[i] + acc1[i];
+    } else if ((WHO & 2) && wave >= 4) {
+        float S[32];
+        for (int i = 0; i < 32; ++i) S[i] = 0.001f * (float)(threadIdx.x + 3 * i);
+        float m = 0.f, l = 0.f;
+        uint32_t P[16];
+        for (int it = 0; it < iters; ++it) {
+            float mx = S[0];
+#pragma unroll
+            for (int i = 1; i < 32; ++i) mx = fmaxf(mx, S[i]);
+            m = fmaxf(m, mx * c);
+#pragma unroll
+            for (int i = 0; i < 32; i += 2) {
+                const float p0 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i], c, -m));
+                const float p1 = __builtin_amdgcn_exp2f(__builtin_fmaf(S[i + 1], c, -m));
+                l += p0 + p1;
+                typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+                const bf16x2 q = {(__bf16)p0, (__bf16)p1};
+                P[i / 2] = __builtin_bit_cast(uint32_t, q);
+            }
+#pragma unroll
+            for (int i = 0; i < 32; ++i) S[i] += (float)(P[i & 15] & 0xff) * 1e-6f + l * 1e-9f;   // the next unit depends on this one
+        }
+        s = l + m + S[5];
+    }
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
 __device__ __forceinline__ void direct_load16(const char* gbase, uint32_t voff, uint32_t lds) {
@@ -190,10 +240,16 @@ int main() {
     if (measure([&] { hipLaunchKernelGGL(attn_loop<0>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_loop)) return 1;
     if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_l2)) return 1;
     if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, (uint32_t)span_big, STAGES, 0.1f); }, 20, 20, &r_hbm)) return 1;
+    Result r_cm, r_cv, r_cb;
+    const int CO_ITERS = 2000;
+    if (measure([&] { hipLaunchKernelGGL(coexec<1>, dim3(NWG), dim3(512), 0, 0, out, CO_ITERS, 0.1f); }, 5, 10, &r_cm)) return 1;
+    if (measure([&] { hipLaunchKernelGGL(coexec<2>, dim3(NWG), dim3(512), 0, 0, out, CO_ITERS, 0.1f); }, 5, 10, &r_cv)) return 1;
+    if (measure([&] { hipLaunchKernelGGL(coexec<3>, dim3(NWG), dim3(512), 0, 0, out, CO_ITERS, 0.1f); }, 5, 10, &r_cb)) return 1;
     const double tf_mfma = (double)NWG * 8 * MF_ITERS * 16 * 32768.0 / (r_mfma.ms * 1e-3) / 1e12;
     auto tf = [&](const Result& r) { return (double)NWG * STAGES * flop_stage / (r.ms * 1e-3) / 1e12; };
     auto tbs = [&](const Result& r) { return (double)NWG * STAGES * 65536.0 / (r.ms * 1e-3) / 1e12; };
-    printf("{\"mfma_only\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
+    printf("{\"coexec_ms\": {\"products_alone\": %.3f, \"vector_work_alone\": %.3f, \"both\": %.3f}, ", r_cm.ms, r_cv.ms, r_cb.ms);
+    printf("\"mfma_only\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
            "\"attn_loop_no_loads\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
            "\"attn_loop_direct_loads_L2\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f, \"load_TBps\": %.2f}, "
            "\"attn_loop_direct_loads_HBM\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f, \"load_TBps\": %.2f}}\n",
