@@ -55,6 +55,20 @@ def test_launch_order_with_null_items(C, L, Hq, Hkv):
     compare(b, out, rows=sample_rows(b, 12, seed=2), label="null items")
 
 
+@pytest.mark.parametrize("k_mult", [6.0, 16.0])
+def test_sharp_logits_exercise_the_reference_maximum(k_mult):
+    """Logits with a standard deviation of 6 and 16 (scale 1/sqrt(d) on keys 6x / 16x too large): the row maximum
+    keeps rising by more than the slack of the lazily raised reference, in wide tiles, narrow items and across
+    key splits, and the softmax is nearly one-hot."""
+    print(f"case: sharp logits x{k_mult}", flush=True)
+    b = W.make_batch([900, 3000, 0, 517], [300, 1, 130, 9], 16, 4, 128, 16, seed=int(k_mult) + 40, k_mult=k_mult, poison=True)
+    db = DevBatch(b)
+    out = run(db)
+    compare(b, out, rows=sample_rows(b, 24, seed=3), label=f"sharp x{k_mult}")
+    out2 = run(DevBatch(b), force_kv_splits=3)
+    compare(b, out2, rows=sample_rows(b, 24, seed=3), label=f"sharp x{k_mult}, 3 key splits")
+
+
 def test_more_requests_than_one_append_launch_carries():
     print("case: 300 decode rows + 3 prefill rows", flush=True)
     rng = np.random.default_rng(3)
