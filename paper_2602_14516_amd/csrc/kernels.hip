@@ -126,7 +126,7 @@ struct RawChunk<KV_FP8> {
 
 struct ItemCtx {
     int req, kvh, g0, gn, q0, nq, kv_begin, kv_end, part_off;
-    int C, L, row_off;
+    int C, row_off;
     const int32_t* bt_row;     // block-table row of the request
 };
 
@@ -142,10 +142,8 @@ __device__ __forceinline__ ItemCtx load_item(const AttnParams& p, int idx) {
     c.kv_begin = it.kv_begin;
     c.kv_end = it.kv_end;
     c.part_off = it.part_off;
-    const ReqInfo ri = p.reqs[it.req];
-    c.C = ri.C;
-    c.L = ri.L;
-    c.row_off = ri.row_off;
+    c.C = it.C;
+    c.row_off = it.row_off;
     c.bt_row = p.block_table + (int64_t)it.req * p.max_pages;
     return c;
 }

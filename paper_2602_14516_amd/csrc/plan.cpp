@@ -108,7 +108,9 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
             it.kv_begin = (int32_t)(sp * chunk);
             it.kv_end = (int32_t)std::min<int64_t>(b.nkeys, (sp + 1) * chunk);
             it.part_off = nsplit > 1 ? (int32_t)(part0 + (int64_t)sp * slot) : -1;
-            it.pad = 0;
+            it.C = out.reqs[b.req].C;
+            it.row_off = out.reqs[b.req].row_off;
+            it.pad[0] = it.pad[1] = it.pad[2] = 0;
             const int64_t keys = it.kv_end - it.kv_begin;
             const int64_t cost = b.kind == KIND_WIDE ? keys * 4 : keys;
             order.push_back(Cost{cost, (int32_t)out.items.size()});
@@ -269,7 +271,7 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                 if (take_wide ? iw >= wide_ix.size() : in >= narrow_ix.size()) break;
                 const int32_t idx = take_wide ? wide_ix[iw++] : narrow_ix[in++];
                 if (idx < 0) {
-                    sorted.push_back(Item{-1, pack_heads(0, 0, 0, KIND_NULL), 0, 0, 0, 0, -1, 0});
+                    sorted.push_back(Item{-1, pack_heads(0, 0, 0, KIND_NULL), 0, 0, 0, 0, -1, 0, 0, {0, 0, 0}});
                     continue;
                 }
                 const Item& it = out.items[idx];

@@ -27,14 +27,17 @@ struct ReqInfo {          // 16 B, one per request, device-visible
     int32_t C, L, row_off, pad;
 };
 
-struct Item {             // 32 B, one per attention workgroup, device-visible
+struct Item {             // 48 B, one per attention workgroup, device-visible
     int32_t req;          // -1 for a null item
     int32_t heads;        // kvh | g0 << 8 | gn << 16 | kind << 24
     int32_t q0, nq;       // first new-token index and token count of this item
     int32_t kv_begin, kv_end;   // key range [begin, end) in logical positions
     int32_t part_off;     // float offset of this item's partial slot, or -1: write final output
-    int32_t pad;
+    int32_t C;            // context length of the request and the first row of its packed q / out rows:
+    int32_t row_off;      // copies of its ReqInfo, so that a workgroup starts with one dependent load less
+    int32_t pad[3];
 };
+static_assert(sizeof(Item) == 48, "device layout");
 
 struct CombItem {         // 32 B, one per query tile whose key range was split
     int32_t req;
