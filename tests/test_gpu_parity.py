@@ -55,6 +55,32 @@ def test_small_shapes_elementwise(name, C, L, Hq, Hkv, d, P):
     compare(db.b, out, label=name)
 
 
+def test_seeded_random_shapes_elementwise():
+    """Sixteen seeded random batches: head geometry, page size, head dim, request count and lengths drawn at random,
+    with lengths biased towards the boundaries of pages (16 / 32), 32-key blocks, 64-key units and 128-key stages.
+    Append bit-exact, attention element-wise against the oracle (sampled rows when a batch is large)."""
+    rng = np.random.default_rng(20260214)
+    edges = np.array([0, 1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513])
+    for case in range(16):
+        Hkv = int(rng.choice([1, 2, 4]))
+        G = int(rng.choice([1, 2, 3, 4, 8, 16]))
+        d = int(rng.choice([64, 128]))
+        P = int(rng.choice([16, 32]))
+        n = int(rng.integers(1, 7))
+        pick = lambda hi: int(rng.choice(edges[edges <= hi])) if rng.random() < 0.6 else int(rng.integers(0, hi + 1))
+        C = [pick(700) for _ in range(n)]
+        L = [pick(300) for _ in range(n)]
+        if sum(L) == 0:
+            L[0] = 1
+        print(f"case {case}: Hq={Hkv * G} Hkv={Hkv} d={d} P={P} C={C} L={L}", flush=True)
+        db = DevBatch(W.make_batch(C, L, Hkv * G, Hkv, d, P, seed=1000 + case, poison=True))
+        fn = A.mixed_batch_attn if case % 2 else A.incr_prefill_attn
+        out = run_attn(db, fn=fn, force_kv_splits=int(rng.choice([0, 0, 2, 5])))
+        check_append(db)
+        rows = sample_rows(db.b, 12, seed=case) if sum(L) * Hkv * G > 6000 else None
+        compare(db.b, out, rows=rows, label=f"random case {case}")
+
+
 @pytest.mark.parametrize("splits", [2, 3, 7])
 def test_forced_kv_splits_match(splits):
     print(f"case: forced splits {splits}", flush=True)
