@@ -38,6 +38,7 @@
 namespace ampd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -150,8 +151,9 @@ __device__ __forceinline__ ItemCtx load_item(const AttnParams& p, int idx) {
 
 // Per-lane state of one wave: 32 query rows (lane % 32), O^T as D/32 accumulator blocks.
 // m is a *reference* maximum in the log2 domain (scale * log2(e) folded in), not the exact
-// running maximum: it is raised (and O, l rescaled) only when some row's block maximum
-// exceeds it by more than RESCALE_SLACK, so probabilities stay below 2^RESCALE_SLACK.
+// running maximum: it is raised (and O, l rescaled) only when probabilities against it would grow too large:
+// narrow items raise it when a block maximum exceeds it by more than RESCALE_SLACK (probabilities stay below
+// 2^RESCALE_SLACK); wide items when a lane's 16 probabilities of a block sum to more than PSUM_LIMIT.
 // (m, l, O) remain a consistent triple, which is all the final normalisation and the split-KV
 // merge need.
 template <int D>
@@ -161,6 +163,7 @@ struct WaveAcc {
     float l;      // this lane's share of the running sum (lanes l and l^32 hold halves)
 };
 constexpr float RESCALE_SLACK = 8.0f;
+constexpr float PSUM_LIMIT = 4096.0f;
 
 // ---------------------------------------------------------------------------------------------
 // the steps of one 32-key block
@@ -221,6 +224,20 @@ __device__ __forceinline__ float exp32(const f32x16& S, float c, float m_use, bf
     return psum;
 }
 
+// The same for the wide path: the sum is taken over the ROUNDED probabilities, two per instruction
+// (dot product of a bf16 pair with (1, 1) accumulated in fp32), which is also what the second product adds up.
+__device__ __forceinline__ float exp32_dot(const f32x16& S, float c, float m_use, bf16x8 (&P)[2], float psum) {
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int i = 0; i < 16; i += 2) {
+        const bf16x2 pr = {(__bf16)fast_exp2(__builtin_fmaf(S[i], c, -m_use)), (__bf16)fast_exp2(__builtin_fmaf(S[i + 1], c, -m_use))};
+        psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+        P[i >> 3][i & 7] = pr[0];
+        P[i >> 3][(i + 1) & 7] = pr[1];
+    }
+    return psum;
+}
+
 // O^T += V^T P^T for the 32 keys whose LDS tile starts at vl.
 // k-slot s of MFMA cc is key 16*cc + 8*(s/4) + 4*(lane/32) + s%4 of the block.
 template <int D>
@@ -260,53 +277,112 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
     pv32<D>(vl, P, st, lane);
 }
 
-// One 64-key tile of a wide item: both 32-key halves share one maximum check, so that the
-// compiler can run the second half's exponentials in the shadow of the first half's O += V P.
-template <int D, bool MASK>
-__device__ __forceinline__ void tile64(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
-                                       float c, int rel, int lane) {
+// ---------------------------------------------------------------------------------------------
+// Software-pipelined processing of one LDS stage by one wave, at 32-key granularity.
+//
+// On this device the vector instructions of the softmax hide behind matrix instructions mostly when both come
+// from the SAME wave, finely interleaved in program order (a SIMD running the products of one wave and the vector
+// work of another needs the products' time plus two thirds of the vector work's time; interleaved in one wave, one
+// quarter).  One pipeline iteration therefore carries, step by step,
+//     one product of S^T(b+1) = K(b+1) Q^T,   the exponentials of a slice of block b,   one product of O^T += V(b-1)^T P(b-1)^T
+// for three consecutive 32-key blocks, with the LDS fragment reads three steps ahead; scheduling fences keep the steps
+// in this order.  The pipeline is filled and drained inside every stage (6 iterations for 4 blocks), because the next
+// stage's K rows are only known to have landed after the barrier that ends this one.
+//
+// The exponentials of a block are taken against the reference the row already has; the block's own maximum is only
+// looked at when that turned out too low (some probability above 2^12: the lane's sum says so) or when the row has
+// no reference yet.  That check sits at the end of the iteration, where S^T(b) is still in registers and O holds the
+// blocks up to b-1: the reference is raised, O and l are rescaled, and P(b) is redone in place.
+template <int D>
+struct PipeState {
+    f32x16 Sa, Sb;          // logits of two consecutive blocks (the roles alternate)
+    bf16x8 Pa[2], Pb[2];    // probabilities of two consecutive blocks
+};
+
+// S_out <- block at kl (QK), P_out <- exp of S_in (SM), O += V(vl) P_prev (PV).
+//   rel_in: (last visible key of the lane's row) - (first key of the block of S_in) - 4 * (lane / 32) (read when MASK).
+template <int D, bool QK, bool SM, bool PV, bool MASK>
+__device__ __forceinline__ void pipe_iter(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
+                                          f32x16& S_in, f32x16& S_out, bf16x8 (&P_out)[2], const bf16x8 (&P_prev)[2],
+                                          float c, int rel_in, int lane) {
     using G_ = Geo<D>;
-    constexpr int NKK = G_::NKK;
-    f32x16 S0, S1;
-    bf16x8 P0[2], P1[2];
-    {
-        // S^T of both 32-key halves with the K fragments of a whole half in flight ahead of the matrix
-        // instructions that use them: the reads of half 1 are issued one by one behind the products of half 0.
-        const int r = lane & 31, g = lane >> 5;
-        const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
-        u32x4 f0[NKK], f1[NKK];
+    constexpr int NS = G_::NKK;                      // steps: one K fragment and one V fragment per step
+    constexpr int LPS = 16 / NS;                     // logits per lane and step
+    constexpr int PF = 3;                            // fragment reads run this many steps ahead (measured: 1 < 2 < 3 = 4 > 5)
+    static_assert(2 * G_::NDB == NS && LPS % 2 == 0, "steps per block");
+    const int g = lane >> 5, r = lane & 31, hi = (lane >> 4) & 1, i16 = lane & 15;
+    const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
+    const int key = 4 * g + (i16 >> 2);
+    const uint32_t va = vl + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + hi * 32 + (i16 & 3) * 8;
+    constexpr int K8 = (8 / G_::KPW) * G_::GS + (8 % G_::KPW) * 64;      // +8 keys
+    constexpr int K16 = (16 / G_::KPW) * G_::GS;                        // +16 keys
+    auto read_k = [&](int kk) { return *LDS_PTR(const u32x4, ka + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32); };
+    auto read_v = [&](int i) {                       // fragment i = cc * NDB + db
+        const uint32_t a0 = va + (i / G_::NDB) * K16 + (i % G_::NDB) * (G_::KPW * 64);
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+        const s16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + K8));
+        return s16x8{lo[0], lo[1], lo[2], lo[3], h4[0], h4[1], h4[2], h4[3]};
+    };
+    u32x4 kf[NS];
+    s16x8 vf[NS];
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) f0[kk] = *LDS_PTR(const u32x4, ka + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32);
+    for (int j = 0; j < PF; ++j) {
+        if (QK) kf[j] = read_k(j);
+        if (PV) vf[j] = read_v(j);
+    }
+    if (SM && MASK) mask32(S_in, rel_in);
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float m_use = st.m == NEG_INF ? 0.0f : st.m;
+    float psum = 0.0f;
 #pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
-            f1[kk] = *LDS_PTR(const u32x4, ka + G_::B32 + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32);
-        S0 = f32x16{0};
-        S1 = f32x16{0};
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
-            S0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f0[kk]), Q[kk], S0, 0, 0, 0);
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk)
-            S1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f1[kk]), Q[kk], S1, 0, 0, 0);
-        __builtin_amdgcn_sched_group_barrier(0x100, NKK, 0);           // NKK LDS reads
-#pragma unroll
-        for (int kk = 0; kk < NKK; ++kk) {
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);         // one matrix instruction
-            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);         // one LDS read
+    for (int j = 0; j < NS; ++j) {
+        if (j + PF < NS) {
+            if (QK) kf[j + PF] = read_k(j + PF);
+            if (PV) vf[j + PF] = read_v(j + PF);
         }
-        __builtin_amdgcn_sched_group_barrier(0x008, NKK, 0);
+        if (QK)
+            S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[j]), Q[j], j == 0 ? f32x16{0} : S_out, 0, 0, 0);
+        if (SM) {
+#pragma unroll
+            for (int i = j * LPS; i < (j + 1) * LPS; i += 2) {
+                const bf16x2 pr = {(__bf16)fast_exp2(__builtin_fmaf(S_in[i], c, -m_use)),
+                                   (__bf16)fast_exp2(__builtin_fmaf(S_in[i + 1], c, -m_use))};
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                P_out[i >> 3][i & 7] = pr[0];
+                P_out[i >> 3][(i + 1) & 7] = pr[1];
+            }
+        }
+        if (PV)
+            st.O[j % G_::NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j]), P_prev[j / G_::NDB],
+                                                                        st.O[j % G_::NDB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
     }
-    if (MASK) {
-        mask32(S0, rel);
-        mask32(S1, rel - 32);
+    if (SM) {
+        if (__any(st.m == NEG_INF || !(psum <= PSUM_LIMIT))) {                    // rare
+            raise_reference<D>(st, rowmax32(S_in) * c);
+            m_use = st.m == NEG_INF ? 0.0f : st.m;
+            psum = exp32_dot(S_in, c, m_use, P_out, 0.0f);
+        }
+        st.l += psum;
     }
-    const float mx = fmaxf(rowmax32(S0), rowmax32(S1)) * c;
-    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference<D>(st, mx);
-    const float m_use = st.m == NEG_INF ? 0.0f : st.m;
-    st.l += exp32(S0, c, m_use, P0);
-    st.l += exp32(S1, c, m_use, P1);
-    pv32<D>(vl, P0, st, lane);
-    pv32<D>(vl + G_::B32, P1, st, lane);
+}
+
+// All blocks of one stage (NB = KT / 32 blocks; K rows at kst, V rows at vst), for one wave.
+// rel0: the lane's `rel` for block 0 of the stage.
+template <int D, bool MASK>
+__device__ __forceinline__ void stage_pipelined(uint32_t kst, uint32_t vst, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
+                                                PipeState<D>& ps, float c, int rel0, int lane) {
+    using G_ = Geo<D>;
+    constexpr int NB = KT / 32;
+    static_assert(NB == 4, "the iterations below are written out for four blocks");
+    const uint32_t B = G_::B32;
+    //           QK     SM     PV
+    pipe_iter<D, true, false, false, MASK>(kst, 0, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, 0, lane);
+    pipe_iter<D, true, true, false, MASK>(kst + B, 0, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, rel0, lane);
+    pipe_iter<D, true, true, true, MASK>(kst + 2 * B, vst, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, rel0 - 32, lane);
+    pipe_iter<D, true, true, true, MASK>(kst + 3 * B, vst + B, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, rel0 - 64, lane);
+    pipe_iter<D, false, true, true, MASK>(0, vst + 2 * B, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, rel0 - 96, lane);
+    pipe_iter<D, false, false, true, MASK>(0, vst + 3 * B, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, 0, lane);
 }
 
 // Load the B operand (Q^T) of one wave: lane holds row lane%32, d = kk*16 + (lane/32)*8 .. +8.
@@ -552,19 +628,17 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
     // Tiles whose last key is visible to every row of the workgroup need no causal select;
     // the remaining (at most a few) tiles around the diagonal take the masked variant.
     const int wg_first = ic.C + ic.q0;                     // smallest last-visible key in the workgroup
-    const int t_diag = min(ntiles, max(0, (wg_first + 1 - k_lo) / KT));
+    const int t_diag = min(min(ntiles, nfull), max(0, (wg_first + 1 - k_lo) / KT));   // (a ragged last stage is masked too)
     Loader<D, KVT, AWG, KT> ld;
+    PipeState<D> ps;
+    // keys from kv_end on (the ragged tail of the last stage) count as masked
+    const int lim_eff = min(lim, ic.kv_end - 1);
     auto compute = [&](int t, uint32_t stage, auto masked) {
-#pragma unroll
-        for (int h = 0; h < KT / 64; ++h) {
-            const int kbase = k_lo + t * KT + h * 64;
-            // skip 64-key halves that lie beyond the key range or that every row of the wave masks
-            if (wave_active && kbase <= w_last && kbase < ic.kv_end) {
-                const int rel = lim - kbase - 4 * (lane >> 5);
-                    tile64<D, decltype(masked)::value>(stage + h * 2 * G_::B32, stage + G_::KTILE + h * 2 * G_::B32, Q, st,
-                                                       p.c_log2, rel, lane);
-            }
-        }
+        const int kbase = k_lo + t * KT;
+        // a wave without rows, or one whose rows all end before this stage, skips it
+        if (wave_active && kbase <= w_last)
+            stage_pipelined<D, decltype(masked)::value>(stage, stage + G_::KTILE, Q, st, ps, p.c_log2,
+                                                        lim_eff - kbase - 4 * (lane >> 5), lane);
     };
     if (DMA) {
         constexpr int AHEAD = NSTAGE - 1;
