@@ -69,6 +69,20 @@ def test_sharp_logits_exercise_the_reference_maximum(k_mult):
     compare(b, out2, rows=sample_rows(b, 24, seed=3), label=f"sharp x{k_mult}, 3 key splits")
 
 
+@pytest.mark.parametrize("per_key,jump_every,jump", [(4.0, 0, 0.0), (0.0, 100, 3000.0), (1.0, 37, 400.0)])
+def test_logits_rising_along_the_keys_keep_raising_the_reference(per_key, jump_every, jump):
+    """Logits that grow with the key position (about +3 per key; steps of ~+2000 every 100 keys, far past the range of
+    exp2 in fp32; both): every block needs a new reference, in the step cases the exponentials taken against the old
+    one overflow first.  Wide tiles, narrow items and key splits."""
+    print(f"case: rising logits {per_key} {jump_every} {jump}", flush=True)
+    b = W.make_batch([900, 3000, 0, 517], [300, 1, 130, 9], 16, 4, 128, 16, seed=71, poison=True)
+    W.impose_key_ramp(b, per_key, jump_every, jump)
+    out = run(DevBatch(b))
+    compare(b, out, rows=sample_rows(b, 24, seed=4), label="rising logits")
+    out2 = run(DevBatch(b), force_kv_splits=3)
+    compare(b, out2, rows=sample_rows(b, 24, seed=4), label="rising logits, 3 key splits")
+
+
 def test_more_requests_than_one_append_launch_carries():
     print("case: 300 decode rows + 3 prefill rows", flush=True)
     rng = np.random.default_rng(3)

@@ -10,7 +10,7 @@ incremental length l_incr per prefill task, one token per decode step; paper Sec
 "System Overview", and Table 1 for the length statistics of the real traces).  Only length
 distributions are synthesised; no item of any dataset is reproduced.
 """
-from .batches import (Batch, make_batch, make_config, config_lengths, CONFIG_SHAPES,
+from .batches import (Batch, make_batch, make_config, config_lengths, CONFIG_SHAPES, impose_key_ramp,
                       f32_to_bf16_bits, bf16_bits_to_f64, BASE_SEED, NAN_BF16)
 from .trace import SessionTrace, make_trace_schedule, draw_tick_tensors
 

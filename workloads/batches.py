@@ -147,6 +147,26 @@ def make_batch(ctx_len, incr_len, Hq, Hkv, d, P, *, seed, scale=None, k_mult=1.0
                  k_pool, v_pool, q, k_new, v_new, name=name, meta={"seed": seed, "poison": poison})
 
 
+
+def impose_key_ramp(b: Batch, per_key: float, jump_every: int = 0, jump: float = 0.0, q0: float = 8.0) -> Batch:
+    """Overwrite channel 0 of every query with q0 and channel 0 of the key at token position t (cached or new) with
+    per_key * t + jump * (t // jump_every), in place: logits then rise along the key axis, steadily and/or in steps,
+    on top of the random part from the other channels."""
+    def level(t):
+        t = np.asarray(t, dtype=np.float64)
+        v = per_key * t
+        if jump_every:
+            v = v + jump * np.floor(t / jump_every)
+        return f32_to_bf16_bits(v.astype(np.float32))
+    b.q[..., 0] = f32_to_bf16_bits(np.full(b.q.shape[:-1], q0, dtype=np.float32))
+    off = b.row_offsets
+    for r in range(b.num_reqs):
+        c, L = int(b.ctx_len[r]), int(b.incr_len[r])
+        t = np.arange(c)
+        b.k_pool[b.block_table[r, t // b.P], :, t % b.P, 0] = level(t)[:, None]
+        b.k_new[off[r]:off[r] + L, :, 0] = level(c + np.arange(L))[:, None]
+    return b
+
 # Layer shapes of the five benchmark configurations.
 CONFIG_SHAPES = {
     1: dict(Hq=8, Hkv=2, d=64, P=16),
