@@ -83,6 +83,17 @@ def test_logits_rising_along_the_keys_keep_raising_the_reference(per_key, jump_e
     compare(b, out2, rows=sample_rows(b, 24, seed=4), label="rising logits, 3 key splits")
 
 
+@pytest.mark.parametrize("Hq,Hkv,d,P", [(8, 2, 64, 32), (6, 2, 64, 16), (32, 1, 128, 32)])
+def test_rising_logits_other_geometries(Hq, Hkv, d, P):
+    """The same ramp + steps with head dimension 64 (four steps per pipeline iteration instead of eight), G = 3 (idle
+    rows in every wave) and G = 32 (one token per wave)."""
+    print(f"case: rising logits Hq={Hq} Hkv={Hkv} d={d} P={P}", flush=True)
+    b = W.make_batch([700, 1500, 0, 333], [260, 1, 150, 40], Hq, Hkv, d, P, seed=72, poison=True)
+    W.impose_key_ramp(b, 1.0, 37, 400.0)
+    out = run(DevBatch(b))
+    compare(b, out, rows=sample_rows(b, 24, seed=5), label="rising logits, geometry")
+
+
 def test_more_requests_than_one_append_launch_carries():
     print("case: 300 decode rows + 3 prefill rows", flush=True)
     rng = np.random.default_rng(3)
