@@ -313,7 +313,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'ceiling' | 'simulate' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'ceiling' | 'simulate' | 'cfg4' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -378,6 +378,28 @@ def main():
             y.copy_(x)
         torch.cuda.synchronize()
         print(json.dumps({"only": "copycal", "bytes_read": x.numel() * 4, "bytes_written": x.numel() * 4}))
+        return
+
+    if args.only == "cfg4":
+        # configuration 4: one GPU's 8/1-head share of a 64/8-head layer, 4 rows of 32-64 k cached tokens + 4096 new
+        # ones; then one decode step (L = 1) over the same rows with their 4096 tokens appended
+        sh4 = W.CONFIG_SHAPES[4]
+        C, L = W.config_lengths(4)
+        res = {}
+        for part, (Cp, Lp) in (("prefill", (C, L)), ("decode_step", (C + L, np.ones_like(L)))):
+            d4 = device_batch(torch, A, W, Cp, Lp, sh4, seed=W.BASE_SEED + 4)
+            fn = make_runner(torch, A, d4, "mixed")
+            ms4 = time_calls(torch, fn, 20 if part == "prefill" else 200, 5)
+            kt4 = kernel_times(torch, A, fn, 5)
+            fl = flops_of(Cp, Lp, sh4["Hq"], sh4["d"])
+            by = bytes_of(Cp, Lp, sh4["Hq"], sh4["Hkv"], sh4["d"], sh4["P"])
+            info = A.plan_describe(d4["cache"], Cp, Lp, d4["bt"].shape[1])
+            res[part] = {"ms_per_step": ms4, "attn_kernel_ms": float(kt4[0]), "combine_ms": float(kt4[1]),
+                         "TFLOPs_attn_kernel": fl / (kt4[0] * 1e-3) / 1e12, "GBps_step": by / (ms4 * 1e-3) / 1e9,
+                         "algorithmic_TFLOP": fl / 1e12, "algorithmic_GB": by / 1e9, "work_items": info["num_items"]}
+            del d4, fn
+            torch.cuda.empty_cache()
+        print(json.dumps({"only": "cfg4", **res}))
         return
 
     # ---- configuration 2: the step that is timed --------------------------------------------

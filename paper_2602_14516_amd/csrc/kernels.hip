@@ -838,6 +838,45 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
 
 constexpr int COMB_ROWS = 16;          // query rows per combine workgroup
 
+// One output quad (4 consecutive d of one row) merged over all splits, UN splits at a time: all loads of a group are
+// issued before any is used, so a thread pays one memory latency per UN splits, and the maximum is carried along
+// (acc and l are rescaled when a group raises it) instead of being taken in a pass of its own.
+template <int D, int UN>
+__device__ __forceinline__ void combine_quad(const float* part0, int nsplit, int64_t stride, int64_t ml_off, int64_t o_off,
+                                             f32x4& acc, float& lsum) {
+    float m_run = NEG_INF;
+    lsum = 0.0f;
+    acc = f32x4{0, 0, 0, 0};
+    for (int s0 = 0; s0 < nsplit; s0 += UN) {
+        float mv[UN], lv[UN];
+        f32x4 ov[UN];
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            const int sp = min(s0 + j, nsplit - 1);                  // the tail re-reads the last split and drops it below
+            const float* base = part0 + (int64_t)sp * stride;
+            mv[j] = base[ml_off];
+            lv[j] = base[ml_off + 1];
+            ov[j] = *reinterpret_cast<const f32x4*>(base + o_off);
+        }
+        float mg = m_run;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) mg = fmaxf(mg, mv[j]);          // (a duplicate of the last split changes nothing)
+        const float muse = mg == NEG_INF ? 0.0f : mg;
+        const float back = fast_exp2(m_run - muse);                  // 0 on the first group
+        lsum *= back;
+        acc *= back;
+#pragma unroll
+        for (int j = 0; j < UN; ++j) {
+            if (s0 + j < nsplit) {
+                const float w = fast_exp2(mv[j] - muse);
+                lsum += lv[j] * w;
+                acc += ov[j] * w;
+            }
+        }
+        m_run = mg;
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
     const CombItem ci = p.combs[blockIdx.x];
@@ -850,45 +889,14 @@ __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
     constexpr int QPR = D / 4;                         // float4 groups per row
     for (int u = threadIdx.x; u < nr * QPR; u += WG) {
         const int r = r0 + u / QPR, dq = (u % QPR) * 4;
-        // The splits are walked four at a time, all loads of a group issued before any is used: with one
-        // load in flight per thread the kernel would pay one memory latency per split, twice.
-        constexpr int UN = 4;
         const float* part0 = p.partial + ci.part_off;
         const int64_t ml_off = (int64_t)rows * D + r * 2;
-        float mall = NEG_INF;
-        for (int s0 = 0; s0 < ci.nsplit; s0 += UN) {
-            float mv[UN];
-#pragma unroll
-            for (int j = 0; j < UN; ++j) {
-                const int sp = min(s0 + j, ci.nsplit - 1);          // the tail re-reads the last split: max is idempotent
-                mv[j] = part0[(int64_t)sp * ci.part_stride + ml_off];
-            }
-#pragma unroll
-            for (int j = 0; j < UN; ++j) mall = fmaxf(mall, mv[j]);
-        }
-        const float muse = mall == NEG_INF ? 0.0f : mall;
-        float lsum = 0.0f;
-        f32x4 acc = {0, 0, 0, 0};
-        for (int s0 = 0; s0 < ci.nsplit; s0 += UN) {
-            float mv[UN], lv[UN];
-            f32x4 ov[UN];
-#pragma unroll
-            for (int j = 0; j < UN; ++j) {
-                const int sp = min(s0 + j, ci.nsplit - 1);
-                const float* base = part0 + (int64_t)sp * ci.part_stride;
-                mv[j] = base[ml_off];
-                lv[j] = base[ml_off + 1];
-                ov[j] = *reinterpret_cast<const f32x4*>(base + (int64_t)r * D + dq);
-            }
-#pragma unroll
-            for (int j = 0; j < UN; ++j) {
-                if (s0 + j < ci.nsplit) {                            // (the tail's duplicate loads are dropped)
-                    const float w = fast_exp2(mv[j] - muse);
-                    lsum += lv[j] * w;
-                    acc += ov[j] * w;
-                }
-            }
-        }
+        float lsum;
+        f32x4 acc;
+        if (ci.nsplit > 8)                                  // long decode contexts: a hundred splits and more
+            combine_quad<D, 16>(part0, ci.nsplit, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
+        else
+            combine_quad<D, 4>(part0, ci.nsplit, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
         const float inv = 1.0f / lsum;
         const int tl = r / gn, hg = r - tl * gn;
         const int hq = kvh * (p.Hq / p.Hkv) + g0 + hg;
