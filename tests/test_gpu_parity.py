@@ -90,6 +90,16 @@ def test_forced_kv_splits_match(splits):
     compare(b, out, label=f"splits{splits}")
 
 
+@pytest.mark.parametrize("splits", [9, 17, 33])
+def test_many_kv_splits_take_the_wide_combine_groups(splits):
+    """More than 8 splits per row (long decode contexts): the combine pass then walks them 16 at a time, with a
+    ragged last group (9 -> 9, 17 -> 16 + 1 or 16, 33 -> 29 splits on the longest row)."""
+    print(f"case: many splits {splits}", flush=True)
+    b = W.make_batch([9000, 4100, 2500], [1, 1, 40], 8, 2, 128, 16, seed=23, poison=True)
+    out = run_attn(DevBatch(b), force_kv_splits=splits)
+    compare(b, out, label=f"splits{splits}")
+
+
 def test_mixed_equals_separate_sub_batches():
     print("case: mixed vs separate", flush=True)
     C = [700, 90, 2048, 5, 300, 1500]
