@@ -293,96 +293,98 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
 // looked at when that turned out too low (some probability above 2^12: the lane's sum says so) or when the row has
 // no reference yet.  That check sits at the end of the iteration, where S^T(b) is still in registers and O holds the
 // blocks up to b-1: the reference is raised, O and l are rescaled, and P(b) is redone in place.
-template <int D>
-struct PipeState {
-    f32x16 Sa, Sb;          // logits of two consecutive blocks (the roles alternate)
-    bf16x8 Pa[2], Pb[2];    // probabilities of two consecutive blocks
-};
 
-// S_out <- block at kl (QK), P_out <- exp of S_in (SM), O += V(vl) P_prev (PV).
-//   rel_in: (last visible key of the lane's row) - (first key of the block of S_in) - 4 * (lane / 32) (read when MASK).
-template <int D, bool QK, bool SM, bool PV, bool MASK>
-__device__ __forceinline__ void pipe_iter(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
-                                          f32x16& S_in, f32x16& S_out, bf16x8 (&P_out)[2], const bf16x8 (&P_prev)[2],
-                                          float c, int rel_in, int lane) {
-    using G_ = Geo<D>;
-    constexpr int NS = G_::NKK;                      // steps: one K fragment and one V fragment per step
-    constexpr int LPS = 16 / NS;                     // logits per lane and step
-    constexpr int PF = 3;                            // fragment reads run this many steps ahead (measured: 1 < 2 < 3 = 4 > 5)
-    static_assert(2 * G_::NDB == NS && LPS % 2 == 0, "steps per block");
-    const int g = lane >> 5, r = lane & 31, hi = (lane >> 4) & 1, i16 = lane & 15;
-    const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
-    const int key = 4 * g + (i16 >> 2);
-    const uint32_t va = vl + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + hi * 32 + (i16 & 3) * 8;
-    constexpr int K8 = (8 / G_::KPW) * G_::GS + (8 % G_::KPW) * 64;      // +8 keys
-    constexpr int K16 = (16 / G_::KPW) * G_::GS;                        // +16 keys
-    auto read_k = [&](int kk) { return *LDS_PTR(const u32x4, ka + (kk >> 1) * (G_::KPW * 64) + (kk & 1) * 32); };
-    auto read_v = [&](int i) {                       // fragment i = cc * NDB + db
-        const uint32_t a0 = va + (i / G_::NDB) * K16 + (i % G_::NDB) * (G_::KPW * 64);
-        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
-        const s16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + K8));
-        return s16x8{lo[0], lo[1], lo[2], lo[3], h4[0], h4[1], h4[2], h4[3]};
-    };
-    u32x4 kf[NS];
-    s16x8 vf[NS];
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        if (QK) kf[j] = read_k(j);
-        if (PV) vf[j] = read_v(j);
-    }
-    if (SM && MASK) mask32(S_in, rel_in);
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-    float m_use = st.m == NEG_INF ? 0.0f : st.m;
-    float psum = 0.0f;
-#pragma unroll
-    for (int j = 0; j < NS; ++j) {
-        if (j + PF < NS) {
-            if (QK) kf[j + PF] = read_k(j + PF);
-            if (PV) vf[j + PF] = read_v(j + PF);
-        }
-        if (QK)
-            S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[j]), Q[j], j == 0 ? f32x16{0} : S_out, 0, 0, 0);
-        if (SM) {
-#pragma unroll
-            for (int i = j * LPS; i < (j + 1) * LPS; i += 2) {
-                const bf16x2 pr = {(__bf16)fast_exp2(__builtin_fmaf(S_in[i], c, -m_use)),
-                                   (__bf16)fast_exp2(__builtin_fmaf(S_in[i + 1], c, -m_use))};
-                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
-                P_out[i >> 3][i & 7] = pr[0];
-                P_out[i >> 3][(i + 1) & 7] = pr[1];
-            }
-        }
-        if (PV)
-            st.O[j % G_::NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[j]), P_prev[j / G_::NDB],
-                                                                        st.O[j % G_::NDB], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (SM) {
-        if (__any(st.m == NEG_INF || !(psum <= PSUM_LIMIT))) {                    // rare
-            raise_reference<D>(st, rowmax32(S_in) * c);
-            m_use = st.m == NEG_INF ? 0.0f : st.m;
-            psum = exp32_dot(S_in, c, m_use, P_out, 0.0f);
-        }
-        st.l += psum;
+// f(integral_constant<int, I>) for I = I0 .. N-1, unrolled at compile time (a runtime loop, even one marked for
+// unrolling, leaves the fragment arrays below indexed at run time, i.e. in scratch memory)
+template <int I, int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
     }
 }
 
-// All blocks of one stage (NB = KT / 32 blocks; K rows at kst, V rows at vst), for one wave.
-// rel0: the lane's `rel` for block 0 of the stage.
+template <int D>
+struct PipeState {
+    f32x16 S[2];            // logits of two consecutive blocks (block b lives in S[b & 1])
+    bf16x8 P[2][2];         // probabilities of two consecutive blocks
+};
+
+// All blocks of one stage (NB = KT / 32 blocks; K rows at kst, V rows at vst), for one wave: NB + 2 iterations of NS
+// steps, written as one flat sequence of steps so that the fragment reads also run ahead across the iterations'
+// ends (only the first PF steps of a stage wait for their LDS reads).  In iteration i, block i is multiplied
+// (QK, i < NB), block i-1 exponentiated (SM), block i-2 multiplied into O (PV).
+//   rel0: (last visible key of the lane's row) - (first key of the stage) - 4 * (lane / 32) (read when MASK).
 template <int D, bool MASK>
 __device__ __forceinline__ void stage_pipelined(uint32_t kst, uint32_t vst, const bf16x8 (&Q)[Geo<D>::NKK], WaveAcc<D>& st,
                                                 PipeState<D>& ps, float c, int rel0, int lane) {
     using G_ = Geo<D>;
     constexpr int NB = KT / 32;
-    static_assert(NB == 4, "the iterations below are written out for four blocks");
-    const uint32_t B = G_::B32;
-    //           QK     SM     PV
-    pipe_iter<D, true, false, false, MASK>(kst, 0, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, 0, lane);
-    pipe_iter<D, true, true, false, MASK>(kst + B, 0, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, rel0, lane);
-    pipe_iter<D, true, true, true, MASK>(kst + 2 * B, vst, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, rel0 - 32, lane);
-    pipe_iter<D, true, true, true, MASK>(kst + 3 * B, vst + B, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, rel0 - 64, lane);
-    pipe_iter<D, false, true, true, MASK>(0, vst + 2 * B, Q, st, ps.Sb, ps.Sa, ps.Pb, ps.Pa, c, rel0 - 96, lane);
-    pipe_iter<D, false, false, true, MASK>(0, vst + 3 * B, Q, st, ps.Sa, ps.Sb, ps.Pa, ps.Pb, c, 0, lane);
+    constexpr int NS = G_::NKK;                      // steps per iteration: one K fragment and one V fragment per step
+    constexpr int LPS = 16 / NS;                     // logits per lane and step
+    constexpr int PF = 3;                            // fragment reads run this many steps ahead (2 to 4 measure alike, 5 and 6 slower)
+    constexpr int NSTEP = (NB + 2) * NS;
+    static_assert(2 * G_::NDB == NS && LPS % 2 == 0, "steps per block");
+    const int g = lane >> 5, r = lane & 31, hi = (lane >> 4) & 1, i16 = lane & 15;
+    const uint32_t ka = kst + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
+    const int key = 4 * g + (i16 >> 2);
+    const uint32_t va = vst + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + hi * 32 + (i16 & 3) * 8;
+    constexpr int K8 = (8 / G_::KPW) * G_::GS + (8 % G_::KPW) * 64;      // +8 keys
+    constexpr int K16 = (16 / G_::KPW) * G_::GS;                        // +16 keys
+    // the fragments step t needs: K fragment t % NS of block t / NS (t < NB * NS), V fragment of block t / NS - 2
+    u32x4 kf[NSTEP];
+    s16x8 vf[NSTEP];
+    auto fetch = [&](int t) {
+        const int i = t / NS, j = t % NS;
+        if (i < NB) kf[t] = *LDS_PTR(const u32x4, ka + i * G_::B32 + (j >> 1) * (G_::KPW * 64) + (j & 1) * 32);
+        if (i >= 2) {                                // fragment j = cc * NDB + db
+            const uint32_t a0 = va + (i - 2) * G_::B32 + (j / G_::NDB) * K16 + (j % G_::NDB) * (G_::KPW * 64);
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+            const s16x4 h4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + K8));
+            vf[t] = s16x8{lo[0], lo[1], lo[2], lo[3], h4[0], h4[1], h4[2], h4[3]};
+        }
+    };
+    static_for<0, PF>([&](auto tc) { fetch(decltype(tc)::value); });
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+    float m_use = 0.0f, psum = 0.0f;
+    static_for<0, NSTEP>([&](auto tc) {
+        constexpr int t = decltype(tc)::value;
+        constexpr int i = t / NS, j = t % NS;
+        constexpr bool QK = i < NB, SM = i >= 1 && i <= NB, PV = i >= 2;
+        f32x16& S_out = ps.S[i & 1];
+        f32x16& S_in = ps.S[(i + 1) & 1];            // block i - 1
+        bf16x8 (&P_out)[2] = ps.P[(i + 1) & 1];
+        const bf16x8 (&P_prev)[2] = ps.P[i & 1];     // block i - 2
+        if constexpr (t + PF < NSTEP) fetch(t + PF);
+        if constexpr (SM && j == 0) {
+            if (MASK) mask32(S_in, rel0 - 32 * (i - 1));
+            m_use = st.m == NEG_INF ? 0.0f : st.m;
+            psum = 0.0f;
+        }
+        if constexpr (QK)
+            S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[t]), Q[j], j == 0 ? f32x16{0} : S_out, 0, 0, 0);
+        if constexpr (SM) {
+#pragma unroll
+            for (int e = j * LPS; e < (j + 1) * LPS; e += 2) {
+                const bf16x2 pr = {(__bf16)fast_exp2(__builtin_fmaf(S_in[e], c, -m_use)),
+                                   (__bf16)fast_exp2(__builtin_fmaf(S_in[e + 1], c, -m_use))};
+                psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
+                P_out[e >> 3][e & 7] = pr[0];
+                P_out[e >> 3][(e + 1) & 7] = pr[1];
+            }
+        }
+        if constexpr (PV)
+            st.O[j % G_::NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[t]), P_prev[j / G_::NDB],
+                                                                        st.O[j % G_::NDB], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (SM && j == NS - 1) {
+            if (__any(st.m == NEG_INF || !(psum <= PSUM_LIMIT))) {                    // rare
+                raise_reference<D>(st, rowmax32(S_in) * c);
+                psum = exp32_dot(S_in, c, st.m == NEG_INF ? 0.0f : st.m, P_out, 0.0f);
+            }
+            st.l += psum;
+        }
+    });
 }
 
 // Load the B operand (Q^T) of one wave: lane holds row lane%32, d = kk*16 + (lane/32)*8 .. +8.
