@@ -425,7 +425,7 @@ def main():
                 "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this same step, scaled by the
                 # copy-kernel calibration (x2.0 / x1.0); see profiles/attn_kernel_cfg2_prefill_counters.md
-                "traffic": 535e6 + 75e6, "traffic_unit": "bytes per launch (algorithmic 0.467e9)",
+                "traffic": 538e6 + 75e6, "traffic_unit": "bytes per launch (algorithmic 0.467e9)",
                 "kernel_ms": float(kt[0]), "combine_ms": float(kt[1]), "append_and_plan_copy_ms": float(kt[2]),
                 "work_items": info["num_items"]}
         roof["frac"] = roof["achieved"] / roof["peak"]
