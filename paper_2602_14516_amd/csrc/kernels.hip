@@ -363,19 +363,27 @@ __device__ __forceinline__ void stage_pipelined(uint32_t kst, uint32_t vst, cons
         }
         if constexpr (QK)
             S_out = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kf[t]), Q[j], j == 0 ? f32x16{0} : S_out, 0, 0, 0);
+        // the slice's exponentials go half before and half behind the second product, so that each half runs in the
+        // shadow of one matrix instruction of this wave
+        float p_even[LPS / 2];
         if constexpr (SM) {
 #pragma unroll
-            for (int e = j * LPS; e < (j + 1) * LPS; e += 2) {
-                const bf16x2 pr = {(__bf16)fast_exp2(__builtin_fmaf(S_in[e], c, -m_use)),
-                                   (__bf16)fast_exp2(__builtin_fmaf(S_in[e + 1], c, -m_use))};
+            for (int h = 0; h < LPS / 2; ++h) p_even[h] = fast_exp2(__builtin_fmaf(S_in[j * LPS + 2 * h], c, -m_use));
+        }
+        if constexpr (SM && PV) __builtin_amdgcn_sched_barrier(0);
+        if constexpr (PV)
+            st.O[j % G_::NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[t]), P_prev[j / G_::NDB],
+                                                                        st.O[j % G_::NDB], 0, 0, 0);
+        if constexpr (SM) {
+#pragma unroll
+            for (int h = 0; h < LPS / 2; ++h) {
+                const int e = j * LPS + 2 * h;
+                const bf16x2 pr = {(__bf16)p_even[h], (__bf16)fast_exp2(__builtin_fmaf(S_in[e + 1], c, -m_use))};
                 psum = __builtin_amdgcn_fdot2_f32_bf16(pr, ones, psum, false);
                 P_out[e >> 3][e & 7] = pr[0];
                 P_out[e >> 3][(e + 1) & 7] = pr[1];
             }
         }
-        if constexpr (PV)
-            st.O[j % G_::NDB] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vf[t]), P_prev[j / G_::NDB],
-                                                                        st.O[j % G_::NDB], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (SM && j == NS - 1) {
             if (__any(st.m == NEG_INF || !(psum <= PSUM_LIMIT))) {                    // rare
