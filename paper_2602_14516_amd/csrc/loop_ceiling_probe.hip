@@ -193,9 +193,11 @@ __global__ __launch_bounds__(512, 1) void attn_loop(float* out, const char* src,
     }
 }
 
+// VPLAIN: 1 = the V fragments are plain 16-byte LDS reads like the K fragments (what a d-major V tile would allow)
+// instead of pairs of transposing 8-byte reads.
 // ACROSS: 0 = six iterations per stage (fill, four blocks, drain), 1 = four full iterations per stage (the pipeline
 // state is carried over the barrier; the V rows that an iteration uses then belong to keys 64 earlier than its K rows).
-template <int ACROSS, int LOADS>
+template <int ACROSS, int LOADS, int VPLAIN = 0>
 __global__ __launch_bounds__(512, 1) void attn_pipe(float* out, const char* src, uint32_t span, int stages, float c) {
     extern __shared__ __attribute__((aligned(16))) char smem_dyn[];
     const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_dyn);
@@ -219,6 +221,7 @@ __global__ __launch_bounds__(512, 1) void attn_pipe(float* out, const char* src,
         constexpr bool QK = decltype(has_qk)::value, SM = decltype(has_sm)::value, PV = decltype(has_pv)::value;
         auto rdk = [&](int j) { return __builtin_bit_cast(bf16x8, *LDS_PTR(const u32x4, kq + j * 1024 + lane * 16)); };
         auto rdv = [&](int j) {
+            if (VPLAIN) return __builtin_bit_cast(bf16x8, *LDS_PTR(const u32x4, vp + j * 1024 + lane * 16));
             const uint32_t a0 = vp + (j / 4) * 4096 + (j % 4) * 1024 + lane * 8;
             const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
             const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + 512));
@@ -357,7 +360,11 @@ int main() {
     if (measure([&] { hipLaunchKernelGGL(attn_loop<0>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_loop)) return 1;
     if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_l2)) return 1;
     if (measure([&] { hipLaunchKernelGGL(attn_loop<1>, dim3(NWG), dim3(512), 131072, 0, out, src, (uint32_t)span_big, STAGES, 0.1f); }, 20, 20, &r_hbm)) return 1;
-    Result r_p0, r_p1, r_p0l2, r_p0hbm;
+    Result r_p0, r_p1, r_p0l2, r_p0hbm, r_pv, r_pvl2;
+    CK(hipFuncSetAttribute((const void*)attn_pipe<0, 0, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    CK(hipFuncSetAttribute((const void*)attn_pipe<0, 1, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
+    if (measure([&] { hipLaunchKernelGGL((attn_pipe<0, 0, 1>), dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_pv)) return 1;
+    if (measure([&] { hipLaunchKernelGGL((attn_pipe<0, 1, 1>), dim3(NWG), dim3(512), 131072, 0, out, src, 1u << 17, STAGES, 0.1f); }, 20, 20, &r_pvl2)) return 1;
     CK(hipFuncSetAttribute((const void*)attn_pipe<0, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
     CK(hipFuncSetAttribute((const void*)attn_pipe<1, 0>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
     CK(hipFuncSetAttribute((const void*)attn_pipe<0, 1>, hipFuncAttributeMaxDynamicSharedMemorySize, 131072));
@@ -382,7 +389,10 @@ int main() {
     printf("\"attn_pipe_no_loads\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
            "\"attn_pipe_across_barrier_no_loads\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
            "\"attn_pipe_direct_loads_L2\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
-           "\"attn_pipe_direct_loads_HBM\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}}\n",
-           tf(r_p0), r_p0.ghz, tf(r_p1), r_p1.ghz, tf(r_p0l2), r_p0l2.ghz, tf(r_p0hbm), r_p0hbm.ghz);
+           "\"attn_pipe_direct_loads_HBM\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
+           "\"attn_pipe_plain_v_reads_no_loads\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}, "
+           "\"attn_pipe_plain_v_reads_direct_loads_L2\": {\"TFLOPs\": %.1f, \"shader_GHz\": %.3f}}\n",
+           tf(r_p0), r_p0.ghz, tf(r_p1), r_p1.ghz, tf(r_p0l2), r_p0l2.ghz, tf(r_p0hbm), r_p0hbm.ghz, tf(r_pv), r_pv.ghz,
+           tf(r_pvl2), r_pvl2.ghz);
     return 0;
 }
