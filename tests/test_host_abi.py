@@ -103,6 +103,23 @@ def test_planner_covers_every_causal_pair_exactly_once(splits):
         coverage_check(Hq, Hkv, d, P, C, L, splits)
 
 
+def test_planner_coverage_on_drawn_shapes():
+    """The same exact-cover property on shapes and lengths drawn by hypothesis (head geometry, page size, a few rows
+    with anything from empty to several query tiles, automatic and forced key splits)."""
+    from hypothesis import given, settings, strategies as st
+
+    geoms = st.sampled_from([(8, 2, 128, 16), (32, 8, 128, 16), (4, 4, 64, 32), (10, 2, 64, 16), (64, 1, 128, 16), (48, 1, 128, 32)])
+    rows = st.lists(st.tuples(st.integers(0, 1500), st.integers(0, 300)), min_size=1, max_size=4)
+
+    @settings(max_examples=25, deadline=None, derandomize=True)
+    @given(geoms, rows, st.sampled_from([0, 0, 3]))
+    def check(geom, cl, splits):
+        Hq, Hkv, d, P = geom
+        coverage_check(Hq, Hkv, d, P, [c for c, _ in cl], [l for _, l in cl], splits)
+
+    check()
+
+
 def test_planner_kinds_and_split_policy():
     c = shape_cache(64, 8, 128, 16)
     C, L = W.config_lengths(3)
