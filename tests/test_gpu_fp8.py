@@ -129,6 +129,54 @@ def test_fp8_append_bit_exact_and_attention_within_tolerance(name, C0, L0, L1, H
 
 
 @pytest.mark.timeout(900)
+def test_seeded_random_fp8_rounds():
+    """Ten seeded random shapes, three rounds each over one pool (a prefill, a second chunk that lands in partly
+    filled pages with larger keys, a decode step), lengths biased towards page / block / stage boundaries, some with
+    forced key splits: pools bit-exact against the E4M3 reference after every round, attention against the oracle on
+    the dequantised cache at the bf16 tolerance."""
+    rng = np.random.default_rng(20260215)
+    edges = np.array([1, 15, 16, 17, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 256, 257, 511, 512, 513])
+    for case in range(10):
+        Hkv = int(rng.choice([1, 2, 4])); G = int(rng.choice([1, 2, 4, 8])); d = int(rng.choice([64, 128])); P = int(rng.choice([16, 32]))
+        Hq, B = Hkv * G, int(rng.integers(1, 5))
+        pick = lambda hi: int(rng.choice(edges[edges <= hi])) if rng.random() < 0.6 else int(rng.integers(1, hi + 1))
+        rounds = [[pick(600) for _ in range(B)], [pick(300) for _ in range(B)], [1] * B]
+        splits = int(rng.choice([0, 0, 3]))
+        print(f"case {case}: Hq={Hq} Hkv={Hkv} d={d} P={P} rounds={rounds} splits={splits}", flush=True)
+        pages = (np.sum(np.array(rounds), axis=0) + P - 1) // P
+        num_pages = int(pages.sum()) + 3
+        perm = rng.permutation(num_pages).astype(np.int32)
+        bt = np.full((B, int(pages.max())), -1, np.int32)
+        o = 0
+        for r in range(B):
+            bt[r, :pages[r]] = perm[o:o + pages[r]]; o += pages[r]
+        scale = 1.0 / np.sqrt(d)
+        pool = Fp8Pool(num_pages, Hq, Hkv, d, P, scale)
+        d_bt = torch.from_numpy(bt).cuda()
+        C = np.zeros(B, np.int32)
+        for step, L_ in enumerate(rounds):
+            L = np.array(L_, np.int32); n = int(L.sum())
+            mag = np.exp2(rng.integers(-2, 1, size=(n, Hkv, 1))).astype(np.float32)
+            q = W.f32_to_bf16_bits(rng.standard_normal((n, Hq, d), dtype=np.float32))
+            k = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, d), dtype=np.float32) * mag * (1.0 + 2 * step))
+            v = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, d), dtype=np.float32) * mag)
+            out = A.mixed_batch_attn(pool.cache, C, L, d_bt, to_dev_bits(q), to_dev_bits(k), to_dev_bits(v),
+                                     block_table_host=bt, force_kv_splits=splits)
+            torch.cuda.synchronize()
+            pool.reference_append(bt, C, L, k, v)
+            pool.assert_equal(bt, C + L)
+            off = np.concatenate([[0], np.cumsum(L)])
+            ref = []
+            for r in range(B):
+                T = int(C[r] + L[r])
+                Kd = oracle.fp8_dequant_request(pool.h_k, pool.h_ks, bt[r], T, P)
+                Vd = oracle.fp8_dequant_request(pool.h_v, pool.h_vs, bt[r], T, P)
+                ref.append(oracle.attn_oracle_request(W.bf16_bits_to_f64(q[off[r]:off[r + 1]]), Kd, Vd, int(C[r]), int(L[r]), scale))
+            mx, mean = errs(from_dev_bits(out), ref, off)
+            assert mx <= TOL_BF16[0] and mean <= TOL_BF16[1], f"case {case} round {step}: {mx:.2e} {mean:.2e}"
+            C = (C + L).astype(np.int32)
+
+
 def test_session_trace_replay_fp8():
     """Configuration 5 at reduced session count: every append and attention call of a multi-round trace goes
     through one persistent fp8 pool; all prefill ticks and a seeded sample of decode ticks are checked."""
