@@ -313,24 +313,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'ceiling' | 'simulate' | 'cfg4' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'simulate' | 'cfg4' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
-
-    if args.only == "ceiling":
-        # stand-alone probe of the wide attention loop's instruction mix: a child process, started before this
-        # process touches the GPU; prints one JSON line
-        import subprocess
-        from paper_2602_14516_amd.build import PROBE
-        if not os.path.exists(PROBE):
-            print("bench.py: build the probe first (python -c 'import __graft_entry__ as g; g.build()')", file=sys.stderr)
-            sys.exit(1)
-        res = subprocess.run([PROBE], stdout=subprocess.PIPE, text=True, timeout=120)
-        print(json.dumps({"only": "ceiling", **json.loads(res.stdout.strip().splitlines()[-1])}))
-        sys.exit(res.returncode)
 
     if args.only == "simulate":
         # host only: the serving simulator on the fitted cost model, three routing policies x reordering on / off

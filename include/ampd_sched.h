@@ -61,8 +61,8 @@ typedef struct {
 #define AMPD_ROUTE_ERROR (-2)
 
 /* Returns AMPD_ROUTE_LOCAL, the index i of the chosen prefill worker, or AMPD_ROUTE_ERROR on invalid
- * input.  costs (optional, [n + 1]) receives t_local followed by t_remote_i; entries are written only
- * when the cost comparison was reached, *reason (optional) gets 0 = TTFT slack, 1 = ITL slack, 2 = cost. */
+ * input.  costs (optional, [n + 1]) receives t_local (Eq. 1) followed by every t_remote_i (Eq. 2); they are
+ * computed on every valid call, whichever rule decides; *reason (optional) gets 0 = TTFT slack, 1 = ITL slack, 2 = cost. */
 int32_t ampd_route(const ampd_route_input *in, ampd_task task, double *costs, int32_t *reason);
 
 typedef struct {

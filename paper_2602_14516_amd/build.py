@@ -55,22 +55,6 @@ def build_sched(force: bool = False) -> str:
     return SCHED_LIB
 
 
-PROBE = os.path.join(HERE, "loop_ceiling_probe")
-PROBE_SRC = os.path.join(CSRC, "loop_ceiling_probe.hip")
-
-
-def build_probe(force: bool = False) -> str:
-    """Compile the stand-alone ceiling probe of the wide attention loop (an executable; `bench.py --only ceiling`)."""
-    if force or not os.path.exists(PROBE) or os.path.getmtime(PROBE) < os.path.getmtime(PROBE_SRC):
-        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17",
-               "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", PROBE_SRC, "-o", PROBE]
-        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-        if res.returncode != 0:
-            raise RuntimeError("hipcc failed:\n" + res.stdout)
-    return PROBE
-
-
 if __name__ == "__main__":
     print(build_sched(force=True))
     print(build(force=True, verbose=True))
-    print(build_probe(force=True))

@@ -417,11 +417,16 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const ItemCtx& ic, i
 // assembly so that the compiler does not track it: its own LDS reads of the *other* pipeline
 // stage would otherwise wait for these loads.  dma_wait() must precede the barrier that
 // publishes the data.  Compiler-issued vmcnt waits stay correct: vector-memory loads retire in
-// order, so extra loads in flight only make them stricter.
+// order, so extra loads in flight only make them stricter.  M0 is named as clobbered so that the compiler never
+// assumes a value of its own survives the statement (it is a reserved register, which the compiler reports with a
+// warning that is silenced here: nothing has to be preserved, M0 is rewritten before every use).
+#pragma clang diagnostic push
+#pragma clang diagnostic ignored "-Winline-asm"
 __device__ __forceinline__ void dma16(const char* gbase, uint32_t voff, uint32_t lds) {
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds), "v"(voff), "s"(gbase)
-                 : "memory");
+                 : "memory", "m0");
 }
+#pragma clang diagnostic pop
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // ---------------------------------------------------------------------------------------------

@@ -21,50 +21,70 @@ double ampd_t_pre(const ampd_tpre_model* m, int32_t l_hist, int32_t l_incr) {
     return (1.0 - w) * t_lo + w * t_hi;
 }
 
-// Algorithm 1.  Lines 1-3: a prefill worker with TTFT slack, in the given random order.  Lines 4-5:
-// local execution if the decode worker has ITL slack.  Lines 6-9: the cheaper of Eq. 1 and Eq. 2.
-int32_t ampd_route(const ampd_route_input* in, ampd_task task, double* costs, int32_t* reason) {
-    if (!in || in->n_prefill_workers < 0 || !in->decode_model) return AMPD_ROUTE_ERROR;
+// Adaptive routing (Algorithm 1 with the cost estimates of Eq. 1 and Eq. 2), in three parts: check the
+// whole input, cost every candidate placement once, then decide.  The decision prefers, in this order, a prefill
+// worker whose windowed TTFT leaves slack (first in the caller's visiting order), the decode worker itself when
+// its windowed ITL leaves slack, and otherwise the cheapest candidate.
+namespace {
+
+double queue_time(const ampd_tpre_model* m, const ampd_task* q, int32_t len) {
+    double t = 0.0;
+    for (int32_t k = 0; k < len; ++k) t += ampd_t_pre(m, q[k].l_hist, q[k].l_incr);
+    return t;
+}
+
+bool route_input_ok(const ampd_route_input* in) {
+    if (!in || in->n_prefill_workers < 0 || !in->decode_model) return false;
     const int n = in->n_prefill_workers;
     if (n > 0 && (!in->ttft_hat || !in->visit_order || !in->prefill_models || !in->kv_d2p || !in->kv_p2d ||
                   !in->remote_queues || !in->remote_queue_len))
-        return AMPD_ROUTE_ERROR;
-    if (in->local_queue_len < 0 || (in->local_queue_len > 0 && !in->local_queue)) return AMPD_ROUTE_ERROR;
-    for (int k = 0; k < n; ++k) {
-        const int i = in->visit_order[k];
-        if (i < 0 || i >= n) return AMPD_ROUTE_ERROR;
-        if (in->ttft_hat[i] <= in->alpha * in->ttft_thres) {
-            if (reason) *reason = 0;
-            return i;
-        }
-    }
-    if (in->itl_hat <= in->beta * in->itl_thres) {
-        if (reason) *reason = 1;
-        return AMPD_ROUTE_LOCAL;
-    }
-    // Eq. 1: the task itself plus everything queued on the decode worker
-    double t_local = ampd_t_pre(in->decode_model, task.l_hist, task.l_incr);
-    for (int k = 0; k < in->local_queue_len; ++k)
-        t_local += ampd_t_pre(in->decode_model, in->local_queue[k].l_hist, in->local_queue[k].l_incr);
-    if (costs) costs[0] = t_local;
-    int32_t best = AMPD_ROUTE_LOCAL;
-    double best_t = t_local;
+        return false;
+    if (in->local_queue_len < 0 || (in->local_queue_len > 0 && !in->local_queue)) return false;
     for (int i = 0; i < n; ++i) {
-        // Eq. 2: prefill + history KV there + incremental KV back + queue
-        double t = ampd_t_pre(&in->prefill_models[i], task.l_hist, task.l_incr);
-        t += in->kv_d2p[i].alpha + in->kv_d2p[i].beta * task.l_hist;
-        t += in->kv_p2d[i].alpha + in->kv_p2d[i].beta * task.l_incr;
-        if (in->remote_queue_len[i] < 0 || (in->remote_queue_len[i] > 0 && !in->remote_queues[i])) return AMPD_ROUTE_ERROR;
-        for (int k = 0; k < in->remote_queue_len[i]; ++k)
-            t += ampd_t_pre(&in->prefill_models[i], in->remote_queues[i][k].l_hist, in->remote_queues[i][k].l_incr);
+        if (in->visit_order[i] < 0 || in->visit_order[i] >= n) return false;
+        if (in->remote_queue_len[i] < 0 || (in->remote_queue_len[i] > 0 && !in->remote_queues[i])) return false;
+    }
+    return true;
+}
+
+}  // namespace
+
+int32_t ampd_route(const ampd_route_input* in, ampd_task task, double* costs, int32_t* reason) {
+    if (!route_input_ok(in)) return AMPD_ROUTE_ERROR;
+    const int n = in->n_prefill_workers;
+
+    // candidate 0 = local (Eq. 1: the task plus everything queued on the decode worker); candidate 1 + i = prefill
+    // worker i (Eq. 2: the task there, its history KV over, its incremental KV back, and that worker's queue)
+    int32_t cheapest = AMPD_ROUTE_LOCAL;
+    double cheapest_t = ampd_t_pre(in->decode_model, task.l_hist, task.l_incr) +
+                        queue_time(in->decode_model, in->local_queue, in->local_queue_len);
+    if (costs) costs[0] = cheapest_t;
+    for (int i = 0; i < n; ++i) {
+        const ampd_tpre_model* m = &in->prefill_models[i];
+        const double t = ampd_t_pre(m, task.l_hist, task.l_incr) + in->kv_d2p[i].alpha + in->kv_d2p[i].beta * task.l_hist +
+                         in->kv_p2d[i].alpha + in->kv_p2d[i].beta * task.l_incr +
+                         queue_time(m, in->remote_queues[i], in->remote_queue_len[i]);
         if (costs) costs[1 + i] = t;
-        if (t < best_t) {
-            best_t = t;
-            best = i;
+        if (t < cheapest_t) {                         // strict: ties stay with the earlier candidate
+            cheapest_t = t;
+            cheapest = i;
         }
     }
-    if (reason) *reason = 2;
-    return best;
+
+    int32_t why = 2, choice = cheapest;
+    if (in->itl_hat <= in->beta * in->itl_thres) {
+        why = 1;
+        choice = AMPD_ROUTE_LOCAL;
+    }
+    for (int k = n - 1; k >= 0; --k) {                // the first worker with slack in visiting order wins
+        const int i = in->visit_order[k];
+        if (in->ttft_hat[i] <= in->alpha * in->ttft_thres) {
+            why = 0;
+            choice = i;
+        }
+    }
+    if (reason) *reason = why;
+    return choice;
 }
 
 // Algorithm 2 with Eq. 3 (completion time of the k-th task of an ordering = prefix sum of the

@@ -234,7 +234,6 @@ def test_config4_long_context_prefill_then_decode_with_and_without_forced_splits
     k1 = W.f32_to_bf16_bits(g.standard_normal((4, b.Hkv, b.d), dtype=np.float32))
     v1 = W.f32_to_bf16_bits(g.standard_normal((4, b.Hkv, b.d), dtype=np.float32))
     need = (C2.astype(np.int64) + 1 + b.P - 1) // b.P
-    assert need.max() <= b.block_table.shape[1] or True
     k_after, v_after = from_dev_bits(db.k_pool), from_dev_bits(db.v_pool)
     bt = b.block_table
     if need.max() > bt.shape[1]:                 # a row whose T was a multiple of P needs one more page

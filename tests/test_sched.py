@@ -63,12 +63,32 @@ def test_reordering_by_hand():
 
 
 def test_reference_reordering_is_optimal_and_respects_caps():
+    # 200 random windows against an enumeration written out here: count the TTFT-satisfying tasks of every ordering
+    # that moves no task with an exhausted counter backwards; the result must reach the best count, be feasible
+    # itself, be the identity when the identity is already best, and raise exactly the counters of the tasks it moved back
     rng = np.random.default_rng(0)
     for _ in range(200):
         n = int(rng.integers(1, 6)); w = int(rng.integers(n, 6))
         window = [(float(rng.uniform(0.01, 0.5)), float(rng.uniform(-1, 0)), int(rng.integers(0, w + 1))) for _ in range(n)]
-        order, counters, s = R.reorder(window, w, 0.0, float(rng.uniform(0.3, 1.5)))
-        thres = None
+        thres = float(rng.uniform(0.3, 1.5))
+        order, counters, s = R.reorder(window, w, 0.0, thres)
+
+        def count(p):
+            t, cnt = 0.0, 0
+            for r in p:
+                t += window[r][0]
+                cnt += (0.0 - window[r][1]) + t <= thres
+            return cnt
+
+        def feasible(p):
+            return all(not (pos > r and window[r][2] >= w) for pos, r in enumerate(p))
+
+        best = max(count(p) for p in itertools.permutations(range(n)) if feasible(p))
+        assert sorted(order) == list(range(n)) and feasible(order)
+        assert s == best == count(order)
+        if count(tuple(range(n))) == best:
+            assert order == list(range(n))
+        assert counters == [window[i][2] + (order.index(i) > i) for i in range(n)]
     # independent exhaustive check on a fixed instance: S of the result equals the max over feasible orders
     window = [(0.3, -0.2, 0), (0.2, -0.5, 2), (0.1, -0.6, 0), (0.25, -0.1, 1)]
     order, counters, s = R.reorder(window, 4, 0.0, 0.8)
