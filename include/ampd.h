@@ -18,10 +18,14 @@
  * Memory model
  *   - Every pointer is labelled HOST or DEVICE.  DEVICE pointers must belong to the GPU
  *     that is current on the calling thread.  The library never frees or retains caller
- *     pointers beyond the stream work it enqueues, and allocates no device memory; it
- *     keeps a small ring of pinned host staging buffers for the work list.
+ *     pointers beyond the stream work it enqueues, and allocates no device memory.  Per
+ *     device it keeps a ring of pinned host staging buffers for the work list (32 x 256 KiB,
+ *     pinned by ampd_init or by the first attention call on that device).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
- *     stream) and the calls return without waiting for the GPU.
+ *     stream) and the calls return without waiting for the GPU: a call takes a staging
+ *     buffer that no enqueued copy still reads (completion is polled), and when all are
+ *     busy it pins one more, so the ring grows to the number of calls the caller keeps in
+ *     flight (at 4096 buffers a call waits for the oldest instead).
  *   - HOST arrays are read before the call returns and may be reused immediately.
  *
  * Layouts
@@ -101,14 +105,24 @@ typedef struct {
     int32_t reserved[7];       /* must be 0 */
 } ampd_plan_options;
 
+/* One-time set-up of the GPU that is current on the calling thread: pins the staging ring.
+ * Optional (every attention call does the same set-up on its first use of a device);
+ * idempotent; thread-safe.
+ * Returns AMPD_OK or AMPD_ERR_HIP. */
+ampd_status ampd_init(void);
+
 /* Bytes of DEVICE workspace the attention calls need for this batch (work list + split-KV
- * partial results).  Pure host computation; returns 0 on invalid arguments. */
+ * partial results), from the task metadata (l_hist, l_incr) alone (paper Section 3: the
+ * scheduler holds these lengths on the CPU).  Pure host computation; returns 0 on invalid
+ * arguments. */
 size_t ampd_workspace_bytes(const ampd_kv_cache *cache, const ampd_batch *batch);
 size_t ampd_workspace_bytes_opts(const ampd_kv_cache *cache, const ampd_batch *batch,
                                  const ampd_plan_options *opts);
 
-/* Merge new K/V rows into the paged cache (the decode worker's merge of incremental KV
- * into its stored history KV): token i of request r is written to position C_r + i.
+/* Merge new K/V rows into the paged cache (paper Section 3, step 2, "Remote execution",
+ * footnote: the decode worker merges the received incremental KV into the history KV it
+ * stores; Section 3, step 4: it then holds all KV of the request): token i of request r is
+ * written to position C_r + i.
  * k_new, v_new: DEVICE bf16 [sum L][Hkv][d].
  * bf16 cache: a bit-exact copy.  8-bit cache: per (page, KV head) and separately for K
  * and V, e = the smallest integer with amax <= 448 * 2^e over the tokens written to that
@@ -134,7 +148,11 @@ ampd_status ampd_kv_unpack(const ampd_kv_cache *cache, const ampd_batch *batch, 
                            int32_t head_count, const void *k_in, const void *v_in, void *stream);
 
 /* Append, then causal GQA attention of the L_r new queries of every row over its C_r + L_r
- * keys (prefill with history l_hist = C_r and incremental length l_incr = L_r).
+ * keys (paper Section 3, performance model T_pre(l_hist, l_incr): a prefill with history
+ * l_hist = C_r and incremental length l_incr = L_r; initial prefill is l_hist = 0).
+ * This and ampd_mixed_batch_attn are one implementation under two names: the planner turns
+ * rows with few query rows into split-KV items and the others into prefill tiles, whatever
+ * the entry point.
  * q: DEVICE bf16 [sum L][Hq][d];  out: DEVICE bf16 [sum L][Hq][d].
  * workspace: DEVICE, 256-byte aligned, >= ampd_workspace_bytes(). */
 ampd_status ampd_incr_prefill_attn(const ampd_kv_cache *cache, const ampd_batch *batch,
@@ -142,8 +160,10 @@ ampd_status ampd_incr_prefill_attn(const ampd_kv_cache *cache, const ampd_batch 
                                    void *out, void *workspace, size_t workspace_bytes,
                                    void *stream);
 
-/* The same operation for a batch that mixes decode rows (L_r = 1) with incremental-prefill
- * rows (L_r > 1) in any order, as a decode instance executing prefills locally sees them:
+/* The same operation for a batch that mixes decode rows (L_r = 1; paper Section 3, T_dec:
+ * one token per request per step) with incremental-prefill rows (L_r > 1) in any order, as
+ * a decode instance executing prefills locally sees them (Section 3, step 2, "Local
+ * execution"):
  * all attention work of the batch, compute-bound prefill tiles and bandwidth-bound decode
  * splits alike, is issued as ONE attention launch (followed by one combine launch when
  * key ranges were split). */
@@ -162,14 +182,16 @@ ampd_status ampd_mixed_batch_attn_opts(const ampd_kv_cache *cache, const ampd_ba
                                        void *out, void *workspace, size_t workspace_bytes,
                                        void *stream, const ampd_plan_options *opts);
 
-/* Attention only (no append): the pools must already hold all C_r + L_r tokens.  Used to
- * time the attention launch alone and after a separate ampd_kv_append. */
+/* Attention only (no append): the pools must already hold all C_r + L_r tokens (the state
+ * after a remote execution's KV merge, paper Section 3, step 2).  Used to time the attention
+ * launch alone and after a separate ampd_kv_append. */
 ampd_status ampd_paged_attn(const ampd_kv_cache *cache, const ampd_batch *batch,
                             const void *q, void *out, void *workspace, size_t workspace_bytes,
                             void *stream, const ampd_plan_options *opts);
 
-/* Description of the work list the planner builds for a batch (host only; for tests and
- * for the benchmark's roofline accounting).  Returns AMPD_OK or a validation error. */
+/* Description of the work list the planner builds for a batch from its (l_hist, l_incr)
+ * metadata (host only; for tests and for the benchmark's roofline accounting).  Returns
+ * AMPD_OK or a validation error. */
 typedef struct {
     int64_t num_items;          /* attention work items (= workgroups of the attention launch), null items included */
     int64_t num_wide_items;     /* prefill tiles: up to 256 query rows, 8 waves share K/V tiles */
@@ -195,7 +217,9 @@ int64_t ampd_plan_items(const ampd_kv_cache *cache, const ampd_batch *batch,
  * and its combine launch on this thread, measured with HIP events recorded on the caller's
  * stream around them.  Only valid after the stream has been synchronised; returns
  * AMPD_ERR_INVALID_ARG if no launch was recorded or timing is disabled.
- * Timing is off by default; ampd_set_timing(1) turns it on. */
+ * Timing is off by default; ampd_set_timing(1) turns it on for the CALLING THREAD only
+ * (the flag and the events are per thread); this is the measurement hook behind the
+ * offline profiling of T_pre / T_dec (paper Section 3, offline stage). */
 void ampd_set_timing(int enabled);
 ampd_status ampd_last_timing(float *attn_ms, float *combine_ms, float *append_ms);
 

@@ -70,13 +70,17 @@ def _bf16_to_f64(bits):
     return u.view(np.float32).astype(np.float64)
 
 
-def fp8_append_reference(codes, scales, block_table, ctx_len, incr_len, x_new, P):
+def fp8_append_reference(codes, scales, block_table, ctx_len, incr_len, x_new, P, in_place=False):
     """Append bf16 rows x_new [sumL, Hkv, d] into an 8-bit pool.
 
     codes [num_pages, Hkv, P, d] uint8 and scales [num_pages, Hkv] float32 are copied, the
-    copies updated page by page in the order described in the module header, and returned."""
-    codes = np.array(codes, copy=True)
-    scales = np.array(scales, dtype=np.float32, copy=True)
+    copies updated page by page in the order described in the module header, and returned.
+    in_place=True updates the given arrays instead (a long replay would otherwise copy the
+    whole pool at every step); the arithmetic is the same."""
+    if not in_place:
+        codes = np.array(codes, copy=True)
+        scales = np.array(scales, dtype=np.float32, copy=True)
+    assert codes.dtype == np.uint8 and scales.dtype == np.float32
     Hkv = codes.shape[1]
     off = 0
     for r in range(len(ctx_len)):

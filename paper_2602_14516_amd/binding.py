@@ -18,6 +18,7 @@ EXPORTED_SYMBOLS = [
     "ampd_incr_prefill_attn", "ampd_mixed_batch_attn", "ampd_incr_prefill_attn_opts",
     "ampd_mixed_batch_attn_opts", "ampd_paged_attn", "ampd_plan_describe", "ampd_plan_items",
     "ampd_set_timing", "ampd_last_timing", "ampd_status_string", "ampd_version", "ampd_kv_pack", "ampd_kv_unpack",
+    "ampd_init",
 ]
 
 AMPD_KV_BF16, AMPD_KV_FP8_E4M3 = 0, 1
@@ -55,11 +56,30 @@ class _PlanInfo(ctypes.Structure):
                                               "partial_bytes", "plan_bytes")]
 
 
+HOST_ONLY_SYMBOLS = ["ampd_workspace_bytes", "ampd_workspace_bytes_opts", "ampd_plan_describe", "ampd_plan_items",
+                     "ampd_status_string", "ampd_version"]
+
+
+class _HostOnly:
+    """Stands in for an entry point that a host-only build of the library (the sanitizer build of the planner and
+    of argument validation: AMPD_HOST_ONLY=1 next to AMPD_LIB_PATH) does not hold: attributes can be set, a call raises."""
+
+    def __init__(self, name):
+        self._name = name
+
+    def __call__(self, *a):
+        raise RuntimeError(f"{self._name} is not part of a host-only build of libampd")
+
+
 def _load():
     if not os.path.exists(LIB_PATH):
-        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_14516_amd.build` "
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python paper_2602_14516_amd/build.py` "
                           "(there is no fallback path)")
     L = ctypes.CDLL(LIB_PATH)
+    if os.environ.get("AMPD_HOST_ONLY") == "1":
+        for name in EXPORTED_SYMBOLS:
+            if name not in HOST_ONLY_SYMBOLS:
+                setattr(L, name, _HostOnly(name))
     vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
     cp, bp, op = ctypes.POINTER(_Cache), ctypes.POINTER(_Batch), ctypes.POINTER(_Opts)
     L.ampd_workspace_bytes.restype = sz
@@ -81,6 +101,8 @@ def _load():
         f.argtypes = [cp, bp, vp, vp, vp, vp, vp, sz, vp, op]
     L.ampd_paged_attn.restype = i32
     L.ampd_paged_attn.argtypes = [cp, bp, vp, vp, vp, sz, vp, op]
+    L.ampd_init.restype = i32
+    L.ampd_init.argtypes = []
     L.ampd_plan_describe.restype = i32
     L.ampd_plan_describe.argtypes = [cp, bp, op, ctypes.POINTER(_PlanInfo)]
     L.ampd_plan_items.restype = i64
@@ -230,6 +252,19 @@ def kv_unpack(cache: KVCache, first_token, num_tokens, block_table, head_begin, 
                               _stream_ptr(stream)), "ampd_kv_unpack")
 
 
+def _temp_workspace(need, q, stream):
+    """A workspace for one call: allocated, and later returned to torch's caching allocator, on the stream the call
+    runs on, so that the block cannot be handed out again while that stream still uses it."""
+    import torch
+    if stream is None or isinstance(stream, int):
+        # a raw hipStream_t cannot be named to the allocator: the caller passes workspace= in that case
+        if isinstance(stream, int) and stream != torch.cuda.current_stream().cuda_stream:
+            raise ValueError("pass workspace= when stream= is a raw stream handle other than torch's current stream")
+        return torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    with torch.cuda.stream(stream):
+        return torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+
+
 def _attn_call(fn_name, cache, ctx_len, incr_len, block_table, q, k_new, v_new, out, workspace, stream,
                block_table_host, force_kv_splits):
     import torch
@@ -240,7 +275,7 @@ def _attn_call(fn_name, cache, ctx_len, incr_len, block_table, q, k_new, v_new, 
         out = torch.empty_like(q)
     if workspace is None:
         need = int(lib.ampd_workspace_bytes_opts(ctypes.byref(c), ctypes.byref(b), o))
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q, stream)
     fn = getattr(lib, fn_name + "_opts")
     _check(fn(ctypes.byref(c), ctypes.byref(b), _ptr(q), _ptr(k_new), _ptr(v_new), _ptr(out), _ptr(workspace),
               workspace.numel() * workspace.element_size(), _stream_ptr(stream), o), fn_name)
@@ -261,6 +296,11 @@ def mixed_batch_attn(cache: KVCache, ctx_len, incr_len, block_table, q, k_new, v
                       workspace, stream, block_table_host, force_kv_splits)
 
 
+def init() -> None:
+    """One-time set-up of the current device (pins the staging ring)."""
+    _check(lib.ampd_init(), "ampd_init")
+
+
 def paged_attn(cache: KVCache, ctx_len, incr_len, block_table, q, *, out=None, workspace=None, stream=None,
                block_table_host=None, force_kv_splits=0):
     """Attention only; the pools must already hold all C + L tokens of every row."""
@@ -272,7 +312,7 @@ def paged_attn(cache: KVCache, ctx_len, incr_len, block_table, q, *, out=None, w
         out = torch.empty_like(q)
     if workspace is None:
         need = int(lib.ampd_workspace_bytes_opts(ctypes.byref(c), ctypes.byref(b), o))
-        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+        workspace = _temp_workspace(need, q, stream)
     _check(lib.ampd_paged_attn(ctypes.byref(c), ctypes.byref(b), _ptr(q), _ptr(out), _ptr(workspace),
                                workspace.numel() * workspace.element_size(), _stream_ptr(stream), o),
            "ampd_paged_attn")

@@ -6,8 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 INCLUDE = os.path.join(os.path.dirname(HERE), "include")
 LIB = os.path.join(HERE, "libampd.so")
-SOURCES = ["kernels.hip", "api.cpp", "plan.cpp"]
-HEADERS = ["kernels.h", "plan.h", os.path.join(INCLUDE, "ampd.h")]
+SOURCES = ["kernels.hip", "api.cpp", "api_host.cpp", "plan.cpp"]
+HEADERS = ["kernels.h", "plan.h", "api_host.h", os.path.join(INCLUDE, "ampd.h")]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 
 
@@ -53,6 +53,27 @@ def build_sched(force: bool = False) -> str:
         subprocess.check_call(["g++", "-O2", "-std=c++17", "-fPIC", "-shared", "-Wall", "-I", INCLUDE,
                                SCHED_SRC, "-o", SCHED_LIB])
     return SCHED_LIB
+
+
+HOST_SAN_LIB = os.path.join(HERE, "libampd_host_san.so")
+SCHED_SAN_LIB = os.path.join(HERE, "libampd_sched_san.so")
+
+
+def build_host_sanitized(address: bool = True):
+    """Compile the host-only code (planner, argument validation and the entry points that never touch a GPU; the
+    scheduling library) with g++ under the undefined-behaviour sanitizer and, unless address=False, the address
+    sanitizer.  Returns (host library, scheduling library, sanitizer runtime to preload or None).  CPU only: the
+    libraries hold no GPU code and export only the host-side entry points."""
+    san = "address,undefined" if address else "undefined"
+    flags = ["g++", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", "-Wall", f"-fsanitize={san}",
+             "-fno-sanitize-recover=undefined", "-fno-omit-frame-pointer", "-I", INCLUDE, "-I", CSRC]
+    subprocess.check_call(flags + [os.path.join(CSRC, "api_host.cpp"), os.path.join(CSRC, "plan.cpp"), "-o", HOST_SAN_LIB])
+    subprocess.check_call(flags + [SCHED_SRC, "-o", SCHED_SAN_LIB])
+    runtime = None
+    if address:
+        runtime = subprocess.check_output(["g++", "-print-file-name=libasan.so"], text=True).strip()
+        runtime = os.path.realpath(runtime)
+    return HOST_SAN_LIB, SCHED_SAN_LIB, runtime
 
 
 if __name__ == "__main__":

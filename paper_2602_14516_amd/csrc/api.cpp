@@ -1,5 +1,6 @@
-// C ABI of libampd (see include/ampd.h): argument validation, work planning, the pinned
-// staging ring that carries the work list to the device, and the kernel launches.
+// C ABI of libampd (see include/ampd.h), device half: the pinned staging ring that carries the work list to the
+// device and the kernel launches.  Argument validation and the entry points that never
+// touch a GPU live in api_host.cpp.
 #include <hip/hip_runtime.h>
 
 #include <cmath>
@@ -8,80 +9,20 @@
 #include <vector>
 
 #include "ampd.h"
+#include "api_host.h"
 #include "kernels.h"
 #include "plan.h"
 
 namespace {
 
 using namespace ampd;
+using namespace ampd::host;
 
-int log2_exact(int x) {
-    int l = 0;
-    while ((1 << l) < x) ++l;
-    return (1 << l) == x ? l : -1;
-}
-
-// ---- validation ------------------------------------------------------------------------------
-
-ampd_status validate(const ampd_kv_cache* c, const ampd_batch* b, bool need_pools) {
-    if (!c || !b) return AMPD_ERR_INVALID_ARG;
-    if (c->num_q_heads <= 0 || c->num_kv_heads <= 0 || c->num_q_heads % c->num_kv_heads != 0) return AMPD_ERR_INVALID_ARG;
-    if (c->num_kv_heads > 255 || c->num_q_heads / c->num_kv_heads > 64) return AMPD_ERR_UNSUPPORTED;
-    if (c->head_dim != 64 && c->head_dim != 128) return AMPD_ERR_UNSUPPORTED;
-    if (c->page_size != 16 && c->page_size != 32 && c->page_size != 64) return AMPD_ERR_UNSUPPORTED;
-    if (c->kv_dtype != AMPD_KV_BF16 && c->kv_dtype != AMPD_KV_FP8_E4M3) return AMPD_ERR_UNSUPPORTED;
-    if (c->reserved != 0 || c->reserved2 != 0) return AMPD_ERR_INVALID_ARG;
-    if (c->num_pages <= 0) return AMPD_ERR_INVALID_ARG;
-    if (!(c->softmax_scale > 0.0f) || !std::isfinite(c->softmax_scale)) return AMPD_ERR_INVALID_ARG;
-    if (need_pools) {
-        if (!c->k_pool || !c->v_pool) return AMPD_ERR_INVALID_ARG;
-        if (c->kv_dtype == AMPD_KV_FP8_E4M3 && (!c->k_scale || !c->v_scale)) return AMPD_ERR_INVALID_ARG;
-    }
-    if (b->num_reqs < 0 || b->max_pages_per_req < 0) return AMPD_ERR_INVALID_ARG;
-    if (b->num_reqs > 0 && (!b->h_ctx_len || !b->h_incr_len)) return AMPD_ERR_INVALID_ARG;
-    if (need_pools && b->num_reqs > 0 && !b->d_block_table) return AMPD_ERR_INVALID_ARG;
-    int64_t sumL = 0;
-    for (int r = 0; r < b->num_reqs; ++r) {
-        const int64_t C = b->h_ctx_len[r], L = b->h_incr_len[r];
-        if (C < 0 || L < 0) return AMPD_ERR_INVALID_ARG;
-        const int64_t T = C + L;
-        if (T > (int64_t)1 << 30) return AMPD_ERR_UNSUPPORTED;
-        const int64_t need = (T + c->page_size - 1) / c->page_size;
-        if (L > 0 && need > b->max_pages_per_req) return AMPD_ERR_INVALID_ARG;
-        sumL += L;
-        if (sumL > (int64_t)1 << 30) return AMPD_ERR_UNSUPPORTED;
-    }
-    if (b->h_block_table) {
-        for (int r = 0; r < b->num_reqs; ++r) {
-            if (b->h_incr_len[r] == 0) continue;
-            const int64_t T = (int64_t)b->h_ctx_len[r] + b->h_incr_len[r];
-            const int64_t need = (T + c->page_size - 1) / c->page_size;
-            const int32_t* row = b->h_block_table + (int64_t)r * b->max_pages_per_req;
-            for (int64_t i = 0; i < need; ++i)
-                if (row[i] < 0 || row[i] >= c->num_pages) return AMPD_ERR_PAGE_RANGE;
-        }
-    }
-    return AMPD_OK;
-}
-
-ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, Plan& plan) {
-    PlanOptions po;
-    if (o) {
-        if (o->force_kv_splits < 0) return AMPD_ERR_INVALID_ARG;
-        for (int i = 0; i < 7; ++i)
-            if (o->reserved[i] != 0) return AMPD_ERR_INVALID_ARG;
-        po.force_kv_splits = o->force_kv_splits;
-    }
-    Shape s{c->num_q_heads, c->num_kv_heads, c->head_dim, c->page_size};
-    build_plan(s, b->num_reqs, b->h_ctx_len, b->h_incr_len, po, plan);
-    if (plan.partial_floats > 0x7fffffff || plan.items.size() > 0x7fffffffu) return AMPD_ERR_UNSUPPORTED;
-    return AMPD_OK;
-}
-
-// ---- pinned staging ring ---------------------------------------------------------------------
-// The work list is built on the host in pinned memory and copied to the caller's workspace by
-// a small upload kernel that reads the pinned buffer directly.  Each call takes the next ring slot; a slot is reused
-// only after the event recorded behind its copy has completed.
+// ---- per-device state: pinned staging ring, static workspace ------------------------------------
+// The work list is built on the host in pinned memory and copied to the workspace by the GPU reading the pinned
+// buffer directly.  Every call takes a ring slot that no enqueued copy still reads: a slot becomes free once the
+// event recorded behind its copy has completed (polled, never waited for).  When every slot is busy the ring grows,
+// so the depth of the ring follows the number of calls the caller keeps in flight.
 
 struct Slot {
     void* host = nullptr;
@@ -89,54 +30,92 @@ struct Slot {
     hipEvent_t ev = nullptr;
     bool pending = false;
 };
-constexpr int RING = 16;
+struct DeviceState {
+    bool ready = false;
+    std::vector<Slot> ring;
+    size_t next = 0;
+};
+constexpr int MAX_DEVICES = 64;
+constexpr size_t SLOT_BYTES = 256u << 10;      // ~5 000 work items; larger plans get a slot of their own size
+constexpr size_t RING_INITIAL = 32;
+constexpr size_t RING_MAX = 4096;              // beyond this many calls in flight a call waits for the oldest
 std::mutex g_mu;
-Slot g_ring[RING];
-int g_next = 0;
+DeviceState g_dev[MAX_DEVICES];
 
-bool g_timing = false;
+thread_local bool t_timing = false;
 thread_local hipEvent_t t_ev[4] = {nullptr, nullptr, nullptr, nullptr};   // append0, attn0, attn1, comb1
 thread_local bool t_valid = false, t_has_append = false;
 
-hipError_t take_slot(size_t bytes, Slot** out) {
-    static bool primed = false;
-    if (!primed) {                            // allocate the whole ring once, not one slot per call
-        primed = true;
-        for (int i = 0; i < RING; ++i) {
-            if (hipHostMalloc(&g_ring[i].host, 1 << 20, hipHostMallocDefault) != hipSuccess) {
-                g_ring[i].host = nullptr;
-                break;
-            }
-            g_ring[i].cap = 1 << 20;
-        }
+hipError_t new_slot(size_t bytes, Slot* s) {
+    size_t cap = SLOT_BYTES;
+    while (cap < bytes) cap <<= 1;
+    hipError_t e = hipHostMalloc(&s->host, cap, hipHostMallocDefault);
+    if (e != hipSuccess) return e;
+    s->cap = cap;
+    e = hipEventCreateWithFlags(&s->ev, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipHostFree(s->host);
+        *s = Slot();
     }
-    Slot& s = g_ring[g_next];
-    g_next = (g_next + 1) % RING;
-    hipError_t e;
-    if (s.pending) {
-        e = hipEventSynchronize(s.ev);
+    return e;
+}
+
+// Set-up of the device that is current on the calling thread (g_mu held): pin the initial ring.  Runs once per device.
+hipError_t ensure_device(DeviceState** out) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+    DeviceState& d = g_dev[dev];
+    if (!d.ready) {
+        d.ring.reserve(RING_INITIAL);
+        while (d.ring.size() < RING_INITIAL) {
+            Slot s;
+            e = new_slot(SLOT_BYTES, &s);
+            if (e != hipSuccess) return e;
+            d.ring.push_back(s);
+        }
+        d.ready = true;
+    }
+    *out = &d;
+    return hipSuccess;
+}
+
+// A slot of at least `bytes` that no copy still reads (g_mu held).
+hipError_t take_slot(DeviceState& d, size_t bytes, bool may_allocate, Slot** out) {
+    const size_t n = d.ring.size();
+    for (size_t k = 0; k < n; ++k) {                   // oldest first: in the steady state the first probe hits
+        Slot& s = d.ring[(d.next + k) % n];
+        if (s.cap < bytes) continue;
+        if (s.pending) {
+            const hipError_t q = hipEventQuery(s.ev);
+            if (q == hipErrorNotReady) continue;
+            if (q != hipSuccess) return q;
+            s.pending = false;
+        }
+        d.next = (d.next + k + 1) % n;
+        *out = &s;
+        return hipSuccess;
+    }
+    if (may_allocate && n < RING_MAX) {
+        Slot s;
+        const hipError_t e = new_slot(bytes, &s);
+        if (e != hipSuccess) return e;
+        d.ring.push_back(s);
+        *out = &d.ring.back();
+        return hipSuccess;
+    }
+    for (size_t k = 0; k < n; ++k) {                   // no allocation allowed (or the ring is at its cap): wait
+        Slot& s = d.ring[(d.next + k) % n];
+        if (s.cap < bytes) continue;
+        const hipError_t e = hipEventSynchronize(s.ev);
         if (e != hipSuccess) return e;
         s.pending = false;
+        d.next = (d.next + k + 1) % n;
+        *out = &s;
+        return hipSuccess;
     }
-    if (s.cap < bytes) {
-        if (s.host) {
-            e = hipHostFree(s.host);
-            if (e != hipSuccess) return e;
-            s.host = nullptr;
-            s.cap = 0;
-        }
-        size_t cap = 1 << 20;                 // 1 MiB covers ~30 k work items: regrowth is rare
-        while (cap < bytes) cap <<= 1;
-        e = hipHostMalloc(&s.host, cap, hipHostMallocDefault);
-        if (e != hipSuccess) return e;
-        s.cap = cap;
-    }
-    if (!s.ev) {
-        e = hipEventCreateWithFlags(&s.ev, hipEventDisableTiming);
-        if (e != hipSuccess) return e;
-    }
-    *out = &s;
-    return hipSuccess;
+    return hipErrorOutOfMemory;                        // no slot of this size exists and none may be made
 }
 
 #define HIP_TRY(x)                              \
@@ -214,10 +193,10 @@ ampd_status check_workspace(const Plan& plan, const void* workspace, size_t work
     return AMPD_OK;
 }
 
-// Stage the work list in a pinned ring slot (the caller holds g_mu and, once the launch that reads the slot
-// is enqueued, records the slot's event and marks it pending).
-ampd_status stage_plan(const Plan& plan, void* workspace, Slot** slot, PendingUpload* up) {
-    HIP_TRY(take_slot((size_t)plan.plan_bytes, slot));
+// Stage the work list in a pinned ring slot of the current device (the caller holds g_mu and, once the launch that
+// reads the slot is enqueued, records the slot's event and marks it pending).
+ampd_status stage_plan(DeviceState& d, const Plan& plan, void* workspace, bool may_allocate, Slot** slot, PendingUpload* up) {
+    HIP_TRY(take_slot(d, (size_t)plan.plan_bytes, may_allocate, slot));
     char* h = static_cast<char*>((*slot)->host);
     std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
     std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(Item));
@@ -232,12 +211,15 @@ ampd_status stage_plan(const Plan& plan, void* workspace, Slot** slot, PendingUp
 ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& plan, const void* q, void* out,
                     void* workspace, hipStream_t st, const void* k_new = nullptr, const void* v_new = nullptr) {
     if (plan.items.empty()) return k_new ? do_append(c, b, k_new, v_new, st) : AMPD_OK;
+    const bool timing = t_timing;
 
     {
         std::lock_guard<std::mutex> lk(g_mu);
+        DeviceState* d = nullptr;
+        HIP_TRY(ensure_device(&d));
         Slot* s = nullptr;
         PendingUpload up;
-        ampd_status vs = stage_plan(plan, workspace, &s, &up);
+        ampd_status vs = stage_plan(*d, plan, workspace, true, &s, &up);
         if (vs != AMPD_OK) return vs;
         if (k_new) {
             vs = do_append(c, b, k_new, v_new, st, 0, 0, -1, &up);     // the work list rides on the append launch
@@ -270,13 +252,13 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     p.c_log2 = c->softmax_scale * 1.44269504088896340736f;
     const int kvt = c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16;
 
-    if (g_timing) HIP_TRY(hipEventRecord(t_ev[1], st));
+    if (timing) HIP_TRY(hipEventRecord(t_ev[1], st));
     HIP_TRY(launch_attn(p, c->head_dim, kvt, (int)plan.items.size(), st));
-    if (g_timing) HIP_TRY(hipEventRecord(t_ev[2], st));
+    if (timing) HIP_TRY(hipEventRecord(t_ev[2], st));
     int comb_rows = 0;
     for (const CombItem& ci : plan.combs) comb_rows = std::max(comb_rows, ci.nq * ((ci.heads >> 16) & 0xff));
     HIP_TRY(launch_combine(p, c->head_dim, (int)plan.combs.size(), comb_rows, st));
-    if (g_timing) {
+    if (timing) {
         HIP_TRY(hipEventRecord(t_ev[3], st));
         t_valid = true;
     }
@@ -301,7 +283,7 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
     hipStream_t st = static_cast<hipStream_t>(stream);
     t_valid = false;
     t_has_append = false;
-    if (g_timing) {
+    if (t_timing) {
         vs = ensure_timing_events();
         if (vs != AMPD_OK) return vs;
         HIP_TRY(hipEventRecord(t_ev[0], st));
@@ -313,17 +295,6 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
 }  // namespace
 
 extern "C" {
-
-size_t ampd_workspace_bytes_opts(const ampd_kv_cache* cache, const ampd_batch* batch, const ampd_plan_options* opts) {
-    if (validate(cache, batch, false) != AMPD_OK) return 0;
-    Plan plan;
-    if (make_plan(cache, batch, opts, plan) != AMPD_OK) return 0;
-    return (size_t)plan.total_bytes;
-}
-
-size_t ampd_workspace_bytes(const ampd_kv_cache* cache, const ampd_batch* batch) {
-    return ampd_workspace_bytes_opts(cache, batch, nullptr);
-}
 
 ampd_status ampd_kv_append(const ampd_kv_cache* cache, const ampd_batch* batch, const void* k_new, const void* v_new,
                            void* stream) {
@@ -386,6 +357,13 @@ ampd_status ampd_mixed_batch_attn(const ampd_kv_cache* cache, const ampd_batch* 
     return append_then_attend(cache, batch, q, k_new, v_new, out, workspace, workspace_bytes, stream, nullptr);
 }
 
+ampd_status ampd_init(void) {
+    std::lock_guard<std::mutex> lk(g_mu);
+    DeviceState* d = nullptr;
+    HIP_TRY(ensure_device(&d));
+    return AMPD_OK;
+}
+
 ampd_status ampd_paged_attn(const ampd_kv_cache* cache, const ampd_batch* batch, const void* q, void* out,
                             void* workspace, size_t workspace_bytes, void* stream, const ampd_plan_options* opts) {
     ampd_status vs = validate(cache, batch, true);
@@ -399,57 +377,14 @@ ampd_status ampd_paged_attn(const ampd_kv_cache* cache, const ampd_batch* batch,
     if (vs != AMPD_OK) return vs;
     t_valid = false;
     t_has_append = false;
-    if (g_timing) {
+    if (t_timing) {
         vs = ensure_timing_events();
         if (vs != AMPD_OK) return vs;
     }
     return do_attn(cache, batch, plan, q, out, workspace, static_cast<hipStream_t>(stream));
 }
 
-ampd_status ampd_plan_describe(const ampd_kv_cache* cache, const ampd_batch* batch, const ampd_plan_options* opts,
-                               ampd_plan_info* info) {
-    if (!info) return AMPD_ERR_INVALID_ARG;
-    ampd_status vs = validate(cache, batch, false);
-    if (vs != AMPD_OK) return vs;
-    Plan plan;
-    vs = make_plan(cache, batch, opts, plan);
-    if (vs != AMPD_OK) return vs;
-    info->num_items = (int64_t)plan.items.size();
-    info->num_wide_items = plan.num_wide;
-    info->num_narrow_items = plan.num_narrow;
-    info->num_combine_items = (int64_t)plan.combs.size();
-    info->num_append_launches = (batch->num_reqs + APPEND_MAX_REQS - 1) / APPEND_MAX_REQS;
-    info->partial_bytes = plan.partial_floats * 4;
-    info->plan_bytes = plan.plan_bytes;
-    return AMPD_OK;
-}
-
-int64_t ampd_plan_items(const ampd_kv_cache* cache, const ampd_batch* batch, const ampd_plan_options* opts,
-                        int32_t* h_items, int64_t max_items) {
-    ampd_status vs = validate(cache, batch, false);
-    if (vs != AMPD_OK) return vs;
-    Plan plan;
-    vs = make_plan(cache, batch, opts, plan);
-    if (vs != AMPD_OK) return vs;
-    const int64_t n = (int64_t)plan.items.size();
-    for (int64_t i = 0; i < n && i < max_items && h_items; ++i) {
-        const Item& it = plan.items[i];
-        int32_t* o = h_items + i * 10;
-        o[0] = it.req;
-        o[1] = (it.heads >> 24) & 0xff;
-        o[2] = it.heads & 0xff;
-        o[3] = (it.heads >> 8) & 0xff;
-        o[4] = (it.heads >> 16) & 0xff;
-        o[5] = it.q0;
-        o[6] = it.nq;
-        o[7] = it.kv_begin;
-        o[8] = it.kv_end;
-        o[9] = it.part_off;
-    }
-    return n;
-}
-
-void ampd_set_timing(int enabled) { g_timing = enabled != 0; }
+void ampd_set_timing(int enabled) { t_timing = enabled != 0; }
 
 ampd_status ampd_last_timing(float* attn_ms, float* combine_ms, float* append_ms) {
     if (!t_valid) return AMPD_ERR_INVALID_ARG;
@@ -463,18 +398,5 @@ ampd_status ampd_last_timing(float* attn_ms, float* combine_ms, float* append_ms
     return AMPD_OK;
 }
 
-const char* ampd_status_string(ampd_status s) {
-    switch (s) {
-        case AMPD_OK: return "ok";
-        case AMPD_ERR_INVALID_ARG: return "invalid argument";
-        case AMPD_ERR_UNSUPPORTED: return "unsupported configuration";
-        case AMPD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
-        case AMPD_ERR_PAGE_RANGE: return "block table entry out of range";
-        case AMPD_ERR_HIP: return "HIP runtime error";
-    }
-    return "unknown status";
-}
-
-const char* ampd_version(void) { return "libampd 0.1 (gfx950)"; }
 
 }  // extern "C"

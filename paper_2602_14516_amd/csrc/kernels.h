@@ -25,8 +25,6 @@ struct AttnParams {
     float c_log2;              // softmax_scale * log2(e)
 };
 
-constexpr int APPEND_MAX_REQS = 128;   // requests per append launch (lengths travel as kernel arguments)
-
 struct AppendParams {
     const void* k_new;         // bf16 [sum L][Hkv][D]
     const void* v_new;

@@ -22,6 +22,7 @@ namespace ampd {
 enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1, KIND_NULL = 2 };
 
 constexpr int ATTN_WAVES = 8;      // waves of an attention workgroup (one workgroup per CU)
+constexpr int APPEND_MAX_REQS = 128;   // requests per append launch (their lengths travel as kernel arguments)
 
 struct ReqInfo {          // 16 B, one per request, device-visible
     int32_t C, L, row_off, pad;

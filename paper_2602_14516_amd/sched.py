@@ -6,7 +6,7 @@ import os
 
 import numpy as np
 
-SCHED_LIB_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "libampd_sched.so")
+SCHED_LIB_PATH = os.environ.get("AMPD_SCHED_LIB_PATH") or os.path.join(os.path.dirname(os.path.abspath(__file__)), "libampd_sched.so")
 SCHED_SYMBOLS = ["ampd_t_pre", "ampd_route", "ampd_reorder"]
 ROUTE_LOCAL, ROUTE_ERROR = -1, -2
 MAX_WINDOW = 8

@@ -181,3 +181,45 @@ def test_runs_on_a_non_default_stream():
         out = A.mixed_batch_attn(db2.cache, b.ctx_len, b.incr_len, db2.bt, db2.q, db2.k_new, db2.v_new, stream=s)
     s.synchronize()
     assert np.array_equal(from_dev_bits(out), ref)
+
+
+def test_many_calls_in_flight_never_wait_for_the_gpu():
+    """64 calls enqueued back to back without a synchronisation (more than the staging ring holds at first): every call
+    returns in bounded host time, the host stays ahead of the GPU for the whole sequence, and all outputs are equal."""
+    import time
+    print("case: 64 calls in flight", flush=True)
+    A.init()
+    Hq, Hkv, d, P, B, Cx, Lx = 32, 8, 128, 16, 8, 8000, 1024
+    pages_per = (Cx + Lx + P - 1) // P
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    rnd = lambda *s: torch.randn(*s, device="cuda", generator=gen).to(torch.bfloat16)
+    k_pool, v_pool = rnd(B * pages_per, Hkv, P, d), rnd(B * pages_per, Hkv, P, d)
+    bt = torch.randperm(B * pages_per, device="cuda", generator=gen).to(torch.int32).view(B, pages_per).contiguous()
+    q, k_new, v_new = rnd(B * Lx, Hq, d), rnd(B * Lx, Hkv, d), rnd(B * Lx, Hkv, d)
+    cache = A.KVCache(Hq, Hkv, d, P, k_pool, v_pool, 1.0 / np.sqrt(d))
+    C, L = np.full(B, Cx, np.int32), np.full(B, Lx, np.int32)
+    ncalls = 64
+    ws = [torch.empty(A.workspace_bytes(cache, C, L, pages_per), dtype=torch.uint8, device="cuda") for _ in range(ncalls)]
+    outs = [torch.empty_like(q) for _ in range(ncalls)]
+    call = lambda i: A.mixed_batch_attn(cache, C, L, bt, q, k_new, v_new, out=outs[i], workspace=ws[i])
+    for i in range(3):
+        call(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    host = []
+    e0.record()
+    t_begin = time.perf_counter()
+    for i in range(ncalls):
+        t0 = time.perf_counter()
+        call(i)
+        host.append(time.perf_counter() - t0)
+    t_host = time.perf_counter() - t_begin
+    e1.record()
+    torch.cuda.synchronize()
+    t_gpu = e0.elapsed_time(e1) * 1e-3
+    print(f"  host {t_host * 1e3:.1f} ms for {ncalls} calls (slowest {max(host) * 1e3:.2f} ms), GPU {t_gpu * 1e3:.1f} ms", flush=True)
+    assert t_gpu > 0.03, "the case is meant to keep the GPU busy for tens of milliseconds"
+    assert t_host < 0.5 * t_gpu, "the host did not stay ahead of the GPU: some call waited"
+    assert max(host) < 0.25 * t_gpu, "one call took a large part of the whole sequence"
+    for i in range(1, ncalls):
+        assert torch.equal(outs[i], outs[0])

@@ -1,7 +1,8 @@
 """GPU parity of the 8-bit KV cache: append bit-exact against the E4M3 reference, attention
-against the fp64 oracle on the unquantised inputs (6e-2 / 6e-3) and on the dequantised
-cache contents (2e-2 / 2e-3), and a replay of a multi-round session trace through one
-persistent pool."""
+against the fp64 oracle on the dequantised cache contents (2e-2 / 2e-3 on every row: the kernel's own error) and
+on the unquantised inputs (6e-2 / 6e-3 on rows that see at least 256 keys, a bound derived from the rounding of V
+on the others: see gpu_util.fp8_row_bounds), and replays of a multi-round session trace through one persistent
+pool, reduced and at the full size of benchmark configuration 5."""
 import numpy as np
 import pytest
 import torch
@@ -9,7 +10,8 @@ import torch
 import oracle
 import paper_2602_14516_amd as A
 import workloads as W
-from gpu_util import to_dev_bits, from_dev_bits, TOL_BF16, TOL_FP8
+from fp8_replay import replay_trace
+from gpu_util import to_dev_bits, from_dev_bits, fp8_row_bounds, Fp8UnquantisedCheck, TOL_BF16, TOL_FP8
 
 pytestmark = pytest.mark.gpu
 
@@ -45,23 +47,13 @@ class Fp8Pool:
         assert np.array_equal(dvs.view(np.uint32), self.h_vs.view(np.uint32)), "V scales differ"
 
 
-MIN_KEYS_UNQ = 256    # rows that see fewer keys are dominated by single E4M3-rounded V rows (half-ulp 2^-4
-                      # relative, i.e. up to ~0.15 absolute for N(0,1) data): no 3-bit-mantissa cache can meet an
-                      # absolute 6e-2 there, so the comparison with UNQUANTISED inputs is graded on the other rows
-
-
-def errs(got_bits, ref_list, off, C=None, min_keys=0):
+def errs(got_bits, ref_list, off):
     got = W.bf16_bits_to_f64(got_bits)
     parts = []
     for r in range(len(ref_list)):
         if ref_list[r] is None or not len(ref_list[r]):
             continue
-        e = np.abs(got[off[r]:off[r + 1]] - ref_list[r])
-        if min_keys:
-            first = max(0, min_keys - 1 - int(C[r]))          # first new token that sees >= min_keys keys
-            e = e[first:]
-        if e.size:
-            parts.append(e.ravel())
+        parts.append(np.abs(got[off[r]:off[r + 1]] - ref_list[r]).ravel())
     e = np.concatenate(parts) if parts else np.zeros(1)
     assert np.isfinite(e).all()
     return float(e.max()), float(e.mean())
@@ -103,23 +95,38 @@ def test_fp8_append_bit_exact_and_attention_within_tolerance(name, C0, L0, L1, H
         pool.reference_append(bt, C, L, k, v)
         pool.assert_equal()
         off = np.concatenate([[0], np.cumsum(L)])
-        ref_unq, ref_deq = [], []
+        ob = from_dev_bits(out)
+        got = W.bf16_bits_to_f64(ob)
+        ref_deq = []
+        unq, vonly = Fp8UnquantisedCheck(), 0.0
+        G = Hq // Hkv
         for r in range(B):
             hist_k[r] = np.concatenate([hist_k[r], k[off[r]:off[r + 1]]]); hist_v[r] = np.concatenate([hist_v[r], v[off[r]:off[r + 1]]])
             T = int(C[r] + L[r])
-            ref_unq.append(oracle.attn_oracle_request(q[off[r]:off[r + 1]], hist_k[r], hist_v[r], int(C[r]), int(L[r]), scale))
+            qf = W.bf16_bits_to_f64(q[off[r]:off[r + 1]])
             Kd = oracle.fp8_dequant_request(pool.h_k, pool.h_ks, bt[r], T, P)
             Vd = oracle.fp8_dequant_request(pool.h_v, pool.h_vs, bt[r], T, P)
-            ref_deq.append(oracle.attn_oracle_request(W.bf16_bits_to_f64(q[off[r]:off[r + 1]]), Kd, Vd, int(C[r]), int(L[r]), scale))
-        ob = from_dev_bits(out)
+            ref_deq.append(oracle.attn_oracle_request(qf, Kd, Vd, int(C[r]), int(L[r]), scale))
+            Vu = W.bf16_bits_to_f64(hist_v[r])
+            rows = np.arange(int(L[r]))
+            # (a) with the cache's K but the unquantised V the probabilities are the kernel's, so the difference is
+            #     sum_j p_j dV_j: bounded on EVERY row, whatever the logits, by 2^-4 max|V| + the bf16 tolerance
+            ref_kd = oracle.attn_oracle_request(qf, Kd, Vu, int(C[r]), int(L[r]), scale)
+            _, bmax, _ = fp8_row_bounds(Vu, int(C[r]), rows, G)
+            ratio = float((np.abs(got[off[r]:off[r + 1]] - ref_kd).max(axis=2) / bmax).max())
+            assert ratio <= 1.0, f"step {step} request {r}: V rounding bound exceeded ({ratio:.2f} x)"
+            vonly = max(vonly, ratio)
+            # (b) against the oracle on the unquantised K and V.  The first round has keys of the configuration's
+            #     magnitude (at most unit variance): the stated 6e-2 / 6e-3 where >= 256 keys are visible, the derived
+            #     bound elsewhere.  The second round multiplies the keys by 4 on purpose (scale raises, re-encoding):
+            #     logits four times as sharp carry four times the rounding of K, which no 3-bit mantissa can hold to
+            #     6e-2; there (a) and the dequantised comparison are what is asserted.
+            if step == 0:
+                ref_u = oracle.attn_oracle_request(qf, W.bf16_bits_to_f64(hist_k[r]), Vu, int(C[r]), int(L[r]), scale)
+                unq.add(got[off[r]:off[r + 1]], ref_u, Vu, int(C[r]), rows, G, label=f"step {step} request {r}")
         mx, mean = errs(ob, ref_deq, off)
         assert mx <= TOL_BF16[0] and mean <= TOL_BF16[1], f"vs dequantised cache: {mx:.2e} {mean:.2e}"
-        mxu, meanu = errs(ob, ref_unq, off, C, MIN_KEYS_UNQ)
-        print(f"  step {step}: vs dequantised {mx:.2e}/{mean:.2e}; vs unquantised {mxu:.2e}/{meanu:.2e}", flush=True)
-        # this case stresses the scale rule with per-token magnitudes spread over 3 octaves; the graded
-        # 6e-2 / 6e-3 bound against unquantised inputs is checked on the configuration's own N(0,1)
-        # distribution in the trace replay below; here the figure is only reported (peaky softmax
-        # rows reproduce single E4M3-rounded V rows, whatever the kernel does).
+        print(f"  step {step}: vs dequantised {mx:.2e}/{mean:.2e}; V-rounding bound used to {vonly:.2f}; " + unq.finish(f"step {step}"), flush=True)
         # re-issuing the same call changes nothing (idempotent append incl. re-encoded old slots)
         out2 = A.mixed_batch_attn(pool.cache, C, L, d_bt, to_dev_bits(q), to_dev_bits(k), to_dev_bits(v), block_table_host=bt)
         torch.cuda.synchronize()
@@ -177,58 +184,45 @@ def test_seeded_random_fp8_rounds():
             C = (C + L).astype(np.int32)
 
 
-def test_session_trace_replay_fp8():
-    """Configuration 5 at reduced session count: every append and attention call of a multi-round trace goes
-    through one persistent fp8 pool; all prefill ticks and a seeded sample of decode ticks are checked."""
-    print("case: session trace replay", flush=True)
-    tr = W.make_trace_schedule(W.BASE_SEED + 5, num_sessions=8, rounds=4, hi=2048, dec_lo=16, dec_hi=48)
+def _replay_on_gpu(tr, **kw):
     Hq, Hkv, d, P = tr.Hq, tr.Hkv, tr.d, tr.P
-    scale = 1.0 / np.sqrt(d)
-    pool = Fp8Pool(tr.num_pages, Hq, Hkv, d, P, scale)
-    hist_k = [np.zeros((0, Hkv, d), np.uint16) for _ in range(tr.num_sessions)]
-    hist_v = [np.zeros((0, Hkv, d), np.uint16) for _ in range(tr.num_sessions)]
+    pool = Fp8Pool(tr.num_pages, Hq, Hkv, d, P, 1.0 / np.sqrt(d))
     d_bt_full = torch.from_numpy(tr.block_table).cuda()
-    rng = np.random.default_rng(55)
-    worst = [0.0, 0.0]
-    worst_deq = [0.0, 0.0]
-    checked = 0
-    for t, tk in enumerate(tr.ticks):
-        q, k, v = W.draw_tick_tensors(tr, t)
-        bt = tr.tick_block_table(t)
-        pool.reference_append(bt, tk.ctx_len, tk.incr_len, k, v)          # host mirror, in lock-step
+
+    def run_tick(t, tk, bt, q, k, v):
         d_bt = d_bt_full[torch.from_numpy(tk.sessions.astype(np.int64)).cuda()].contiguous()
-        out = A.mixed_batch_attn(pool.cache, tk.ctx_len, tk.incr_len, d_bt, to_dev_bits(q), to_dev_bits(k), to_dev_bits(v),
-                                 block_table_host=bt)
-        off = np.concatenate([[0], np.cumsum(tk.incr_len)])
-        for i, s in enumerate(tk.sessions):
-            hist_k[s] = np.concatenate([hist_k[s], k[off[i]:off[i + 1]]]); hist_v[s] = np.concatenate([hist_v[s], v[off[i]:off[i + 1]]])
-        is_prefill_tick = bool((tk.incr_len > 1).any())
-        if is_prefill_tick or rng.random() < 0.05:
-            torch.cuda.synchronize()
-            ob = from_dev_bits(out)
-            refs = []
-            for i, s in enumerate(tk.sessions):
-                L = int(tk.incr_len[i]); C = int(tk.ctx_len[i])
-                rows = None if L <= 8 else np.unique(np.concatenate([[0, L - 1], rng.integers(0, L, 6)])).astype(np.int32)
-                ref = oracle.attn_oracle_request(q[off[i]:off[i + 1]], hist_k[s], hist_v[s], C, L, scale, rows=rows)
-                got = W.bf16_bits_to_f64(ob[off[i]:off[i + 1]])
-                if rows is not None:
-                    got = got[rows]
-                Kd = oracle.fp8_dequant_request(pool.h_k, pool.h_ks, bt[i], C + L, P)
-                Vd = oracle.fp8_dequant_request(pool.h_v, pool.h_vs, bt[i], C + L, P)
-                ed = np.abs(got - oracle.attn_oracle_request(W.bf16_bits_to_f64(q[off[i]:off[i + 1]]), Kd, Vd, C, L, scale, rows=rows))
-                worst_deq[0] = max(worst_deq[0], float(ed.max())); worst_deq[1] = max(worst_deq[1], float(ed.mean()))
-                e = np.abs(got - ref)
-                assert np.isfinite(e).all()
-                idx = np.arange(L) if rows is None else rows
-                e = e[C + idx + 1 >= MIN_KEYS_UNQ]
-                if e.size:
-                    worst[0] = max(worst[0], float(e.max())); worst[1] = max(worst[1], float(e.mean()))
-            checked += 1
+        return A.mixed_batch_attn(pool.cache, tk.ctx_len, tk.incr_len, d_bt, to_dev_bits(q), to_dev_bits(k), to_dev_bits(v),
+                                  block_table_host=bt)
+
+    def fetch(out):
+        torch.cuda.synchronize()
+        return from_dev_bits(out)
+
+    mir, report = replay_trace(tr, run_tick, fetch, **kw)
     torch.cuda.synchronize()
-    print(f"  {len(tr.ticks)} ticks, {checked} checked: worst max-abs {worst[0]:.2e}, worst per-row mean-abs {worst[1]:.2e}", flush=True)
-    print(f"  against the dequantised cache (all rows): worst max-abs {worst_deq[0]:.2e}, worst per-row mean-abs {worst_deq[1]:.2e}", flush=True)
-    assert worst[0] <= TOL_FP8[0] and worst[1] <= TOL_FP8[1]
-    assert worst_deq[0] <= TOL_BF16[0] and worst_deq[1] <= TOL_BF16[1]
-    # the pool's final byte image equals the reference replay of all appends
+    print("  " + report, flush=True)
+    # the pool's final byte image equals the reference replay of all appends (codes and scales, every page)
+    pool.h_k, pool.h_v, pool.h_ks, pool.h_vs = mir.k, mir.v, mir.ks, mir.vs
     pool.assert_equal()
+
+
+def test_session_trace_replay_fp8_reduced():
+    """Configuration 5 at reduced size (8 sessions x 4 rounds, L <= 2048, 16-48 decode steps): every append and attention
+    call goes through one persistent 8-bit pool; all prefill ticks and a seeded 25 % of the decode ticks are checked."""
+    print("case: session trace replay (reduced)", flush=True)
+    tr = W.make_trace_schedule(W.BASE_SEED + 5, num_sessions=8, rounds=4, hi=2048, dec_lo=16, dec_hi=48)
+    _replay_on_gpu(tr, decode_tick_fraction=0.25, progress_every=0)
+
+
+@pytest.mark.timeout(900)
+def test_config5_full_size_trace_replay_fp8():
+    """Configuration 5 at its stated size: 32 sessions x 8 rounds, tool outputs ~ lognormal(median 512, sigma 1) clipped
+    to [16, 8192], 64-256 decode steps per round, one ampd_mixed_batch_attn call per tick through ONE persistent 8-bit
+    pool.  Checked: every prefill tick (each prefill row on its first, last and 6 random query positions, plus 3 sampled
+    decode rows of the tick) and a seeded 5 % of the decode-only ticks, against the oracle on the dequantised cache
+    (2e-2 / 2e-3) and on the unquantised inputs (6e-2 / 6e-3 where >= 256 keys are visible, the derived bound
+    elsewhere); the pool's byte image (codes and scales of all pages) bit-exact at the end."""
+    print("case: configuration 5, full-size session trace replay", flush=True)
+    tr = W.make_trace_schedule(W.BASE_SEED + 5)
+    assert tr.num_sessions == 32 and len(tr.ticks) > 1000
+    _replay_on_gpu(tr)

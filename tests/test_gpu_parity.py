@@ -202,6 +202,29 @@ def test_config2_full_size_sampled_rows_and_append():
 
 
 @pytest.mark.timeout(900)
+def test_config2_full_size_every_row():
+    """Configuration 2 at full size, in the launch configuration bench.py times, compared with the oracle on EVERY
+    query position and head (about 0.67 TFLOP of fp64 oracle work: minutes on the host cores)."""
+    print("case: config 2 full size, every row", flush=True)
+    b = W.make_config(2)
+    out = run_attn(DevBatch(b))
+    got = W.bf16_bits_to_f64(out)
+    off = b.row_offsets
+    worst, total, count = 0.0, 0.0, 0
+    for r in range(b.num_reqs):                        # one request at a time keeps the fp64 copies small
+        ref = oracle.attn_oracle(b.k_pool, b.v_pool, b.block_table, b.ctx_len, b.incr_len, b.q, b.k_new, b.v_new, b.P, b.scale,
+                                 rows={r: np.arange(int(b.incr_len[r]), dtype=np.int32)})[r]
+        g = got[off[r]:off[r + 1]]
+        assert np.isfinite(g).all()
+        e = np.abs(g - ref)
+        assert e.max() <= TOL_BF16[0], f"request {r}: max-abs {e.max():.3e}"
+        worst, total, count = max(worst, float(e.max())), total + float(e.sum()), count + e.size
+        print(f"  request {r} (C={int(b.ctx_len[r])}, L={int(b.incr_len[r])}): max-abs {e.max():.2e}", flush=True)
+    assert total / count <= TOL_BF16[1]
+    print(f"cfg2, all {off[-1]} query positions x {b.Hq} heads: max-abs {worst:.2e} mean-abs {total / count:.2e}", flush=True)
+
+
+@pytest.mark.timeout(900)
 def test_config3_full_size_mixed_batch():
     print("case: config 3 full size (mixed, one fused launch)", flush=True)
     b, db, out = _full_config(3, fn=A.mixed_batch_attn, per_req=4)
