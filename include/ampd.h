@@ -20,12 +20,14 @@
  *     that is current on the calling thread.  The library never frees or retains caller
  *     pointers beyond the stream work it enqueues, and allocates no device memory.  Per
  *     device it keeps a ring of pinned host staging buffers for the work list (32 x 256 KiB,
- *     pinned by ampd_init or by the first attention call on that device).
+ *     pinned by ampd_init or by the first attention call on that device) and one static
+ *     device array of AMPD_STATIC_WORKSPACE_BYTES (see ampd_mixed_batch_attn_static).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and the calls return without waiting for the GPU: a call takes a staging
  *     buffer that no enqueued copy still reads (completion is polled), and when all are
  *     busy it pins one more, so the ring grows to the number of calls the caller keeps in
- *     flight (at 4096 buffers a call waits for the oldest instead).
+ *     flight (at 4096 buffers a call waits for the oldest instead).  The one exception is
+ *     ampd_mixed_batch_attn_static, which may not allocate and waits for the oldest buffer.
  *   - HOST arrays are read before the call returns and may be reused immediately.
  *
  * Layouts
@@ -63,7 +65,8 @@ typedef enum {
     AMPD_ERR_UNSUPPORTED = -2,   /* head_dim not in {64,128}, page_size not in {16,32,64}, unknown kv_dtype */
     AMPD_ERR_WORKSPACE = -3,     /* workspace NULL, misaligned (256 B) or smaller than ampd_workspace_bytes() */
     AMPD_ERR_PAGE_RANGE = -4,    /* host mirror of the block table holds an id outside [0, num_pages) */
-    AMPD_ERR_HIP = -5            /* a HIP runtime call failed */
+    AMPD_ERR_HIP = -5,           /* a HIP runtime call failed */
+    AMPD_ERR_NOT_INITIALISED = -6 /* ampd_mixed_batch_attn_static before ampd_init on this device */
 } ampd_status;
 
 typedef enum { AMPD_KV_BF16 = 0, AMPD_KV_FP8_E4M3 = 1 } ampd_kv_dtype;
@@ -105,9 +108,9 @@ typedef struct {
     int32_t reserved[7];       /* must be 0 */
 } ampd_plan_options;
 
-/* One-time set-up of the GPU that is current on the calling thread: pins the staging ring.
- * Optional (every attention call does the same set-up on its first use of a device);
- * idempotent; thread-safe.
+/* One-time set-up of the GPU that is current on the calling thread: pins the staging ring and
+ * resolves the static workspace.  Optional for every call except ampd_mixed_batch_attn_static
+ * (the others do the same set-up on their first use of a device); idempotent; thread-safe.
  * Returns AMPD_OK or AMPD_ERR_HIP. */
 ampd_status ampd_init(void);
 
@@ -171,6 +174,25 @@ ampd_status ampd_mixed_batch_attn(const ampd_kv_cache *cache, const ampd_batch *
                                   const void *q, const void *k_new, const void *v_new,
                                   void *out, void *workspace, size_t workspace_bytes,
                                   void *stream);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): ampd_mixed_batch_attn with the work list
+ * and the split-KV partial results in a static device array of AMPD_STATIC_WORKSPACE_BYTES
+ * that the library's code object carries (one copy per GPU, held until the process ends)
+ * instead of a caller workspace.  The call allocates nothing, on the device or pinned:
+ * ampd_init must have run on the current device (else AMPD_ERR_NOT_INITIALISED), and when all
+ * staging buffers of the ring are still being read it waits for the oldest.  Batches whose
+ * ampd_workspace_bytes() exceeds AMPD_STATIC_WORKSPACE_BYTES, or whose work list exceeds one
+ * 256 KiB staging buffer (~5 000 work items), are rejected with AMPD_ERR_WORKSPACE before
+ * anything is enqueued.  Results are bitwise those of ampd_mixed_batch_attn.  All calls on one
+ * GPU share the array: calls on the same stream are ordered and safe, calls that overlap on
+ * different streams of one GPU race.  Nothing in the array has to start at zero (every
+ * partial result is written before it is read), so it is never cleared. */
+#define AMPD_STATIC_WORKSPACE_BYTES (32u << 20)
+ampd_status ampd_mixed_batch_attn_static(const ampd_kv_cache *cache, const ampd_batch *batch,
+                                         const void *q, const void *k_new, const void *v_new,
+                                         void *out, void *stream);
+size_t ampd_static_workspace_limit(void);   /* AMPD_STATIC_WORKSPACE_BYTES of the loaded library */
 
 /* Variants taking planner options (NULL = defaults). */
 ampd_status ampd_incr_prefill_attn_opts(const ampd_kv_cache *cache, const ampd_batch *batch,

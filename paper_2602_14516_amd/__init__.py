@@ -5,9 +5,9 @@ see include/ampd.h).  There is no CPU or PyTorch fallback: if the shared library
 been built, importing the binding raises.
 """
 from .binding import (KVCache, kv_append, kv_pack, kv_unpack, incr_prefill_attn, mixed_batch_attn, paged_attn,
-                      init, workspace_bytes, plan_describe, plan_items, set_timing, last_timing,
+                      init, mixed_batch_attn_static, static_workspace_limit, workspace_bytes, plan_describe, plan_items, set_timing, last_timing,
                       status_string, version, AmpdError, lib, LIB_PATH, EXPORTED_SYMBOLS)
 
 __all__ = ["KVCache", "kv_append", "kv_pack", "kv_unpack", "incr_prefill_attn", "mixed_batch_attn", "paged_attn",
-           "init", "workspace_bytes", "plan_describe", "plan_items", "set_timing", "last_timing",
+           "init", "mixed_batch_attn_static", "static_workspace_limit", "workspace_bytes", "plan_describe", "plan_items", "set_timing", "last_timing",
            "status_string", "version", "AmpdError", "lib", "LIB_PATH", "EXPORTED_SYMBOLS"]

@@ -18,7 +18,7 @@ EXPORTED_SYMBOLS = [
     "ampd_incr_prefill_attn", "ampd_mixed_batch_attn", "ampd_incr_prefill_attn_opts",
     "ampd_mixed_batch_attn_opts", "ampd_paged_attn", "ampd_plan_describe", "ampd_plan_items",
     "ampd_set_timing", "ampd_last_timing", "ampd_status_string", "ampd_version", "ampd_kv_pack", "ampd_kv_unpack",
-    "ampd_init",
+    "ampd_init", "ampd_mixed_batch_attn_static", "ampd_static_workspace_limit",
 ]
 
 AMPD_KV_BF16, AMPD_KV_FP8_E4M3 = 0, 1
@@ -103,6 +103,10 @@ def _load():
     L.ampd_paged_attn.argtypes = [cp, bp, vp, vp, vp, sz, vp, op]
     L.ampd_init.restype = i32
     L.ampd_init.argtypes = []
+    L.ampd_static_workspace_limit.restype = sz
+    L.ampd_static_workspace_limit.argtypes = []
+    L.ampd_mixed_batch_attn_static.restype = i32
+    L.ampd_mixed_batch_attn_static.argtypes = [cp, bp, vp, vp, vp, vp, vp]
     L.ampd_plan_describe.restype = i32
     L.ampd_plan_describe.argtypes = [cp, bp, op, ctypes.POINTER(_PlanInfo)]
     L.ampd_plan_items.restype = i64
@@ -297,8 +301,22 @@ def mixed_batch_attn(cache: KVCache, ctx_len, incr_len, block_table, q, k_new, v
 
 
 def init() -> None:
-    """One-time set-up of the current device (pins the staging ring)."""
+    """One-time set-up of the current device (pins the staging ring, resolves the static workspace)."""
     _check(lib.ampd_init(), "ampd_init")
+
+
+def static_workspace_limit() -> int:
+    return int(lib.ampd_static_workspace_limit())
+
+
+def mixed_batch_attn_static(cache: KVCache, ctx_len, incr_len, block_table, q, k_new, v_new, out, *, stream=None,
+                            block_table_host=None):
+    """mixed_batch_attn on the library's static workspace: the call allocates nothing (out is required)."""
+    b, keep = _batch(ctx_len, incr_len, block_table, block_table_host)
+    c = cache.c_struct()
+    _check(lib.ampd_mixed_batch_attn_static(ctypes.byref(c), ctypes.byref(b), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                            _ptr(out), _stream_ptr(stream)), "ampd_mixed_batch_attn_static")
+    return out
 
 
 def paged_attn(cache: KVCache, ctx_len, incr_len, block_table, q, *, out=None, workspace=None, stream=None,

@@ -1,5 +1,5 @@
 // C ABI of libampd (see include/ampd.h), device half: the pinned staging ring that carries the work list to the
-// device and the kernel launches.  Argument validation and the entry points that never
+// device, the static workspace, and the kernel launches.  Argument validation and the entry points that never
 // touch a GPU live in api_host.cpp.
 #include <hip/hip_runtime.h>
 
@@ -22,7 +22,13 @@ using namespace ampd::host;
 // The work list is built on the host in pinned memory and copied to the workspace by the GPU reading the pinned
 // buffer directly.  Every call takes a ring slot that no enqueued copy still reads: a slot becomes free once the
 // event recorded behind its copy has completed (polled, never waited for).  When every slot is busy the ring grows,
-// so the depth of the ring follows the number of calls the caller keeps in flight.
+// so the depth of the ring follows the number of calls the caller keeps in flight; only a call that may not
+// allocate (the static-workspace entry point) waits for the oldest slot instead.
+
+// Device memory that the static-workspace entry point uses in place of a caller-provided workspace.  On the host
+// this name is only a handle for hipGetSymbolAddress: the address that kernels and copies take is the one
+// that call returns on each device.
+static __device__ __align__(256) unsigned char g_static_workspace[AMPD_STATIC_WORKSPACE_BYTES];
 
 struct Slot {
     void* host = nullptr;
@@ -32,6 +38,7 @@ struct Slot {
 };
 struct DeviceState {
     bool ready = false;
+    void* static_ws = nullptr;         // device address of g_static_workspace on this device
     std::vector<Slot> ring;
     size_t next = 0;
 };
@@ -60,7 +67,8 @@ hipError_t new_slot(size_t bytes, Slot* s) {
     return e;
 }
 
-// Set-up of the device that is current on the calling thread (g_mu held): pin the initial ring.  Runs once per device.
+// Set-up of the device that is current on the calling thread (g_mu held): resolve the static workspace and pin the
+// initial ring.  Runs once per device.
 hipError_t ensure_device(DeviceState** out) {
     int dev = 0;
     hipError_t e = hipGetDevice(&dev);
@@ -68,6 +76,10 @@ hipError_t ensure_device(DeviceState** out) {
     if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
     DeviceState& d = g_dev[dev];
     if (!d.ready) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(g_static_workspace));
+        if (e != hipSuccess) return e;
+        d.static_ws = p;
         d.ring.reserve(RING_INITIAL);
         while (d.ring.size() < RING_INITIAL) {
             Slot s;
@@ -208,18 +220,29 @@ ampd_status stage_plan(DeviceState& d, const Plan& plan, void* workspace, bool m
 }
 
 // plan: already built and checked against the workspace.  append: the K/V rows to append first (or null).
+// workspace == nullptr selects the static workspace of the current device; that path allocates nothing (the
+// device must have been set up by ampd_init) and records no timing events.
 ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& plan, const void* q, void* out,
                     void* workspace, hipStream_t st, const void* k_new = nullptr, const void* v_new = nullptr) {
     if (plan.items.empty()) return k_new ? do_append(c, b, k_new, v_new, st) : AMPD_OK;
-    const bool timing = t_timing;
+    const bool use_static = workspace == nullptr;
+    const bool timing = t_timing && !use_static;
 
     {
         std::lock_guard<std::mutex> lk(g_mu);
         DeviceState* d = nullptr;
-        HIP_TRY(ensure_device(&d));
+        if (use_static) {
+            int dev = -1;
+            HIP_TRY(hipGetDevice(&dev));
+            if (dev < 0 || dev >= MAX_DEVICES || !g_dev[dev].ready) return AMPD_ERR_NOT_INITIALISED;
+            d = &g_dev[dev];
+            workspace = d->static_ws;
+        } else {
+            HIP_TRY(ensure_device(&d));
+        }
         Slot* s = nullptr;
         PendingUpload up;
-        ampd_status vs = stage_plan(*d, plan, workspace, true, &s, &up);
+        ampd_status vs = stage_plan(*d, plan, workspace, !use_static, &s, &up);
         if (vs != AMPD_OK) return vs;
         if (k_new) {
             vs = do_append(c, b, k_new, v_new, st, 0, 0, -1, &up);     // the work list rides on the append launch
@@ -265,9 +288,10 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     return AMPD_OK;
 }
 
+// use_static: take the static workspace of the current device instead of (workspace, workspace_bytes)
 ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, const void* q, const void* k_new,
                                const void* v_new, void* out, void* workspace, size_t workspace_bytes, void* stream,
-                               const ampd_plan_options* opts) {
+                               const ampd_plan_options* opts, bool use_static = false) {
     ampd_status vs = validate(c, b, true);
     if (vs != AMPD_OK) return vs;
     int64_t sumL = 0;
@@ -278,12 +302,18 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
     Plan plan;
     vs = make_plan(c, b, opts, plan);
     if (vs != AMPD_OK) return vs;
-    vs = check_workspace(plan, workspace, workspace_bytes);
-    if (vs != AMPD_OK) return vs;
+    if (use_static) {
+        if ((size_t)plan.total_bytes > (size_t)AMPD_STATIC_WORKSPACE_BYTES || (size_t)plan.plan_bytes > SLOT_BYTES)
+            return AMPD_ERR_WORKSPACE;
+        workspace = nullptr;
+    } else {
+        vs = check_workspace(plan, workspace, workspace_bytes);
+        if (vs != AMPD_OK) return vs;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     t_valid = false;
     t_has_append = false;
-    if (t_timing) {
+    if (t_timing && !use_static) {
         vs = ensure_timing_events();
         if (vs != AMPD_OK) return vs;
         HIP_TRY(hipEventRecord(t_ev[0], st));
@@ -362,6 +392,13 @@ ampd_status ampd_init(void) {
     DeviceState* d = nullptr;
     HIP_TRY(ensure_device(&d));
     return AMPD_OK;
+}
+
+size_t ampd_static_workspace_limit(void) { return (size_t)AMPD_STATIC_WORKSPACE_BYTES; }
+
+ampd_status ampd_mixed_batch_attn_static(const ampd_kv_cache* cache, const ampd_batch* batch, const void* q,
+                                         const void* k_new, const void* v_new, void* out, void* stream) {
+    return append_then_attend(cache, batch, q, k_new, v_new, out, nullptr, 0, stream, nullptr, true);
 }
 
 ampd_status ampd_paged_attn(const ampd_kv_cache* cache, const ampd_batch* batch, const void* q, void* out,

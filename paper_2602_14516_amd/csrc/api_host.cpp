@@ -140,6 +140,7 @@ const char* ampd_status_string(ampd_status s) {
         case AMPD_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
         case AMPD_ERR_PAGE_RANGE: return "block table entry out of range";
         case AMPD_ERR_HIP: return "HIP runtime error";
+        case AMPD_ERR_NOT_INITIALISED: return "ampd_init has not been called on this device";
     }
     return "unknown status";
 }
