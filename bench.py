@@ -316,7 +316,7 @@ def kv_transfer(torch, A, W):
     return {"only": "kvtransfer", "tokens": int(T.sum()), "runs": out}
 
 
-def measure_cfg4(torch, A, W):
+def measure_cfg4(torch, A, W, keep=None):
     """Configuration 4: one GPU's 8/1-head share of a 64/8-head layer, 4 rows of 32-64 k cached tokens + 4096 new
     ones (MFMA-bound, key ranges of the tiles split); then one decode step (L = 1) over the same rows with their 4096
     tokens appended (split-KV decode; ~117 MB of K/V, latency- and launch-bound, reported and not graded)."""
@@ -337,12 +337,15 @@ def measure_cfg4(torch, A, W):
                      "mfma_frac_step": fl / (ms4 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                      "GBps_step": by / (ms4 * 1e-3) / 1e9, "algorithmic_TFLOP": fl / 1e12, "algorithmic_GB": by / 1e9,
                      "work_items": info["num_items"], "combine_items": info["num_combine_items"]}
-        del d4, fn
-        torch.cuda.empty_cache()
+        if keep is not None:
+            keep.append((d4, fn))              # freed by the caller later: a free idles the GPU
+        else:
+            del d4, fn
+            torch.cuda.empty_cache()
     return res
 
 
-def measure_cfg3(torch, A, W, parts):
+def measure_cfg3(torch, A, W, parts, keep=None):
     """Configuration 3: the 96 decode rows alone (the decode-dominated batch: GB/s against HBM), the 8 prefill rows
     alone, the full mixed batch in one fused launch, and the decode rows over an 8-bit cache."""
     sh3 = W.CONFIG_SHAPES[3]
@@ -363,8 +366,11 @@ def measure_cfg3(torch, A, W, parts):
                      "hbm_frac_attn_kernel": by / (kt3[0] * 1e-3) / 1e9 / PEAK_HBM_GBS,
                      "TFLOPs_step": fl3 / (ms3 * 1e-3) / 1e12, "joint_roofline_ms": t_roof,
                      "frac_of_joint_roofline": t_roof / ms3}
-        del d3, fn
-        torch.cuda.empty_cache()
+        if keep is not None:
+            keep.append((d3, fn))
+        else:
+            del d3, fn
+            torch.cuda.empty_cache()
     return out
 
 
@@ -490,16 +496,20 @@ def main():
         return
 
     # The other configurations are measured first and the timed steps of configuration 2 come last, so that the
-    # timed region starts on a GPU that has been busy (its clocks take tens of milliseconds to ramp after idling).
+    # timed region starts on a GPU that has been busy (its clocks take tens of milliseconds to ramp after idling);
+    # for the same reason their buffers are only freed afterwards (a free synchronises and idles the GPU).
     cfg4 = mixed = trace = None
+    keep = []
     if not args.no_mixed:
         trace = trace_replay(torch, A, W)
-        cfg4 = measure_cfg4(torch, A, W)
-        mixed = measure_cfg3(torch, A, W, ("decode", "decode_fp8", "prefill3", "mixed"))
+        cfg4 = measure_cfg4(torch, A, W, keep)
+        mixed = measure_cfg3(torch, A, W, ("decode", "decode_fp8", "prefill3", "mixed"), keep)
         mixed["fused_vs_separate"] = (mixed["decode"]["ms_per_step"] + mixed["prefill3"]["ms_per_step"]) / mixed["mixed"]["ms_per_step"]
 
     ms = time_calls(torch, step, args.steps, args.warmup)
     kt = kernel_times(torch, A, step, min(args.steps, 20))
+    keep.clear()
+    torch.cuda.empty_cache()
     host_ms = host_call_ms(A, db)
     info = A.plan_describe(db["cache"], batch.ctx_len, batch.incr_len, batch.block_table.shape[1])
     big = batch.incr_len >= 256

@@ -156,6 +156,10 @@ ampd_status ampd_kv_unpack(const ampd_kv_cache *cache, const ampd_batch *batch, 
  * This and ampd_mixed_batch_attn are one implementation under two names: the planner turns
  * rows with few query rows into split-KV items and the others into prefill tiles, whatever
  * the entry point.
+ * bf16 cache: the page writes ride in the attention launch as work items of their own and the
+ * attention items read the new tokens from k_new / v_new (which, like every DEVICE argument,
+ * must stay valid until the call's stream work is done).  8-bit cache: a quantising append
+ * launch runs first and attention reads the quantised pages.
  * q: DEVICE bf16 [sum L][Hq][d];  out: DEVICE bf16 [sum L][Hq][d].
  * workspace: DEVICE, 256-byte aligned, >= ampd_workspace_bytes(). */
 ampd_status ampd_incr_prefill_attn(const ampd_kv_cache *cache, const ampd_batch *batch,
@@ -219,16 +223,19 @@ typedef struct {
     int64_t num_wide_items;     /* prefill tiles: up to 256 query rows, 8 waves share K/V tiles */
     int64_t num_narrow_items;   /* decode-style items: <= 32 query rows, 8 waves split the keys */
     int64_t num_combine_items;  /* query tiles whose key range was split */
-    int64_t num_append_launches;
+    int64_t num_append_launches; /* append launches that precede the attention launch (8-bit cache; 0 for bf16) */
     int64_t partial_bytes;      /* split-KV partial results inside the workspace */
     int64_t plan_bytes;         /* work list inside the workspace */
+    int64_t num_append_items;   /* bf16 cache: page-write items (64 packed rows each) that close the attention launch */
 } ampd_plan_info;
 ampd_status ampd_plan_describe(const ampd_kv_cache *cache, const ampd_batch *batch,
                                const ampd_plan_options *opts, ampd_plan_info *info);
 
-/* Copy the planner's attention items, in launch order, to a HOST array of 10 int32 per item:
- * {request, kind (0 wide, 1 narrow, 2 null), kv_head, first_head_in_group, heads, first_token, tokens,
+/* Copy the work items of an append-then-attend call, in launch order, to a HOST array of 10 int32 per item:
+ * {request, kind (0 wide, 1 narrow, 2 null, 3 append), kv_head, first_head_in_group, heads, first_token, tokens,
  *  key_begin, key_end, partial_offset (-1: the item writes final output)};
+ * an append item (bf16 cache) copies `tokens` consecutive packed rows of k_new / v_new, starting at new token
+ * `first_token` of `request` and running on into the following requests, into their pages;
  * a null item (request -1) does no work: workgroup i runs on accelerator die i % 8, and null items keep
  * the wide items that follow on the die whose L2 holds their K/V stream;
  * writes at most max_items items, returns the total number (or a negative ampd_status). */

@@ -227,6 +227,9 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     if (plan.items.empty()) return k_new ? do_append(c, b, k_new, v_new, st) : AMPD_OK;
     const bool use_static = workspace == nullptr;
     const bool timing = t_timing && !use_static;
+    // bf16 cache: the page writes are append items of the attention launch (the plan holds them), and the attention
+    // items read the new tokens from k_new / v_new; 8-bit cache: a quantising append launch goes first
+    const bool fused_append = k_new && plan.num_append > 0;
 
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -244,7 +247,7 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
         PendingUpload up;
         ampd_status vs = stage_plan(*d, plan, workspace, !use_static, &s, &up);
         if (vs != AMPD_OK) return vs;
-        if (k_new) {
+        if (k_new && !fused_append) {
             vs = do_append(c, b, k_new, v_new, st, 0, 0, -1, &up);     // the work list rides on the append launch
             if (vs != AMPD_OK) return vs;
         }
@@ -258,6 +261,8 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     std::memset(&p, 0, sizeof(p));
     p.q = q;
     p.out = out;
+    p.k_new = fused_append ? k_new : nullptr;
+    p.v_new = fused_append ? v_new : nullptr;
     p.k_pool = c->k_pool;
     p.v_pool = c->v_pool;
     p.k_scale = c->k_scale;
@@ -300,7 +305,7 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
     if (!q || !k_new || !v_new || !out) return AMPD_ERR_INVALID_ARG;
     // check the workspace before anything is enqueued
     Plan plan;
-    vs = make_plan(c, b, opts, plan);
+    vs = make_plan(c, b, opts, true, plan);
     if (vs != AMPD_OK) return vs;
     if (use_static) {
         if ((size_t)plan.total_bytes > (size_t)AMPD_STATIC_WORKSPACE_BYTES || (size_t)plan.plan_bytes > SLOT_BYTES)
@@ -406,7 +411,7 @@ ampd_status ampd_paged_attn(const ampd_kv_cache* cache, const ampd_batch* batch,
     ampd_status vs = validate(cache, batch, true);
     if (vs != AMPD_OK) return vs;
     Plan plan;
-    vs = make_plan(cache, batch, opts, plan);
+    vs = make_plan(cache, batch, opts, false, plan);
     if (vs != AMPD_OK) return vs;
     if (plan.items.empty()) return AMPD_OK;
     if (!q || !out) return AMPD_ERR_INVALID_ARG;

@@ -56,8 +56,9 @@ ampd_status validate(const ampd_kv_cache* c, const ampd_batch* b, bool need_pool
     return AMPD_OK;
 }
 
-ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, Plan& plan) {
+ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, Plan& plan) {
     PlanOptions po;
+    po.append_items = with_append && c->kv_dtype == AMPD_KV_BF16;
     if (o) {
         if (o->force_kv_splits < 0) return AMPD_ERR_INVALID_ARG;
         for (int i = 0; i < 7; ++i)
@@ -81,7 +82,7 @@ extern "C" {
 size_t ampd_workspace_bytes_opts(const ampd_kv_cache* cache, const ampd_batch* batch, const ampd_plan_options* opts) {
     if (validate(cache, batch, false) != AMPD_OK) return 0;
     Plan plan;
-    if (make_plan(cache, batch, opts, plan) != AMPD_OK) return 0;
+    if (make_plan(cache, batch, opts, true, plan) != AMPD_OK) return 0;
     return (size_t)plan.total_bytes;
 }
 
@@ -95,13 +96,14 @@ ampd_status ampd_plan_describe(const ampd_kv_cache* cache, const ampd_batch* bat
     ampd_status vs = validate(cache, batch, false);
     if (vs != AMPD_OK) return vs;
     Plan plan;
-    vs = make_plan(cache, batch, opts, plan);
+    vs = make_plan(cache, batch, opts, true, plan);
     if (vs != AMPD_OK) return vs;
     info->num_items = (int64_t)plan.items.size();
     info->num_wide_items = plan.num_wide;
     info->num_narrow_items = plan.num_narrow;
     info->num_combine_items = (int64_t)plan.combs.size();
-    info->num_append_launches = (batch->num_reqs + APPEND_MAX_REQS - 1) / APPEND_MAX_REQS;
+    info->num_append_items = plan.num_append;
+    info->num_append_launches = plan.num_append > 0 ? 0 : (batch->num_reqs + APPEND_MAX_REQS - 1) / APPEND_MAX_REQS;
     info->partial_bytes = plan.partial_floats * 4;
     info->plan_bytes = plan.plan_bytes;
     return AMPD_OK;
@@ -112,7 +114,7 @@ int64_t ampd_plan_items(const ampd_kv_cache* cache, const ampd_batch* batch, con
     ampd_status vs = validate(cache, batch, false);
     if (vs != AMPD_OK) return vs;
     Plan plan;
-    vs = make_plan(cache, batch, opts, plan);
+    vs = make_plan(cache, batch, opts, true, plan);
     if (vs != AMPD_OK) return vs;
     const int64_t n = (int64_t)plan.items.size();
     for (int64_t i = 0; i < n && i < max_items && h_items; ++i) {

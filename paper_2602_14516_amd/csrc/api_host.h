@@ -11,7 +11,9 @@ namespace host {
 int log2_exact(int x);                                   // log2 of a power of two, -1 otherwise
 // need_pools: also require the device pointers an entry point that enqueues work dereferences
 ampd_status validate(const ampd_kv_cache* c, const ampd_batch* b, bool need_pools);
-ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, Plan& plan);
+// with_append: plan an append-then-attend call; for a bf16 cache the page writes then ride in the attention launch
+// as append items (an 8-bit cache quantises in a launch of its own first)
+ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, Plan& plan);
 
 }  // namespace host
 }  // namespace ampd

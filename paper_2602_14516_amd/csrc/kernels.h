@@ -12,6 +12,8 @@ enum : int { KV_BF16 = 0, KV_FP8 = 1 };
 struct AttnParams {
     const void* q;             // bf16 [sum L][Hq][D]
     void* out;                 // bf16 [sum L][Hq][D]
+    const void* k_new;         // bf16 [sum L][Hkv][D]: the new tokens of this call when their page writes ride in the
+    const void* v_new;         //   attention launch (bf16 cache; keys >= C are then read from here), else null
     const void* k_pool;        // [pages][Hkv][P][D]
     const void* v_pool;
     const float* k_scale;      // [pages][Hkv] (8-bit cache) or null

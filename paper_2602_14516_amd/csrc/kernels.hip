@@ -128,8 +128,11 @@ struct RawChunk<KV_FP8> {
 struct ItemCtx {
     int req, kvh, g0, gn, q0, nq, kv_begin, kv_end, part_off;
     int C, row_off;
+    int c_rows;                // keys from this position on are read from the packed new rows (k_new / v_new), not from
+                               // the pages: C when the page writes of this call ride in the same launch, else "never"
     const int32_t* bt_row;     // block-table row of the request
 };
+constexpr int NEVER = 0x3fffffff;
 
 __device__ __forceinline__ ItemCtx load_item(const AttnParams& p, int idx) {
     const Item it = p.items[idx];
@@ -145,6 +148,7 @@ __device__ __forceinline__ ItemCtx load_item(const AttnParams& p, int idx) {
     c.part_off = it.part_off;
     c.C = it.C;
     c.row_off = it.row_off;
+    c.c_rows = p.k_new ? it.C : NEVER;
     c.bt_row = p.block_table + (int64_t)it.req * p.max_pages;
     return c;
 }
@@ -485,8 +489,23 @@ struct Loader {
         r.vb = static_cast<const char*>(p.v_pool) + row;
         return r;
     }
+    // The same group when its keys are new tokens of this call: packed rows [token][Hkv][D] of k_new / v_new (bf16
+    // cache only).  The base is the row of the group's first key (for a group that straddles C it lies before the
+    // request's first row and is only ever used by lanes whose key is >= C); consecutive keys are Hkv rows apart.
+    __device__ __forceinline__ Row new_row_of(const AttnParams& p, const ItemCtx& ic, const Row& r) const {
+        Row n = r;
+        const int64_t off = (((int64_t)ic.row_off + (r.key0 - ic.C)) * p.Hkv + ic.kvh) * (D * 2);
+        n.kb = reinterpret_cast<const char*>(reinterpret_cast<intptr_t>(p.k_new) + off);
+        n.vb = reinterpret_cast<const char*>(reinterpret_cast<intptr_t>(p.v_new) + off);
+        return n;
+    }
+    __device__ __forceinline__ static uint32_t new_lane_off(const AttnParams& p, int t) {
+        const int l = t & 63;
+        return (uint32_t)(((l >> 2) % KPW) * p.Hkv * D * 2 + ((l / (4 * KPW)) * 4 + (l & 3)) * 16);
+    }
 
     // ---- register-staged path
+    // FULL: the whole tile lies inside the key range and in the pages
     template <bool FULL>
     __device__ __forceinline__ void fetch_kv_impl(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
         const uint32_t lo = lane_off(t);
@@ -499,9 +518,15 @@ struct Loader {
                 ks[ps] = p.k_scale[(int64_t)r.page * p.Hkv + ic.kvh];
                 vs[ps] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
             }
-            if (FULL || r.key0 + ((t & 63) >> 2) % KPW < ic.kv_end) {
+            const int key = r.key0 + ((t & 63) >> 2) % KPW;
+            if (FULL || (key < ic.kv_end && key < ic.c_rows)) {
                 k[ps].load(r.kb, lo);
                 v[ps].load(r.vb, lo);
+            } else if (KVT == KV_BF16 && key < ic.kv_end) {      // a new token of this call: read its packed row
+                const Row n = new_row_of(p, ic, r);
+                const uint32_t nlo = new_lane_off(p, t);
+                k[ps].load(n.kb, nlo);
+                v[ps].load(n.vb, nlo);
             } else {
                 k[ps].zero();                                    // keys past the item's end: zeros, so
                 v[ps].zero();                                    // that 0-weights never meet NaN garbage
@@ -509,7 +534,7 @@ struct Loader {
         }
     }
     __device__ __forceinline__ void fetch_kv(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
-        if (kbase + NKEYS <= ic.kv_end)                          // uniform: whole tile inside the key range
+        if (kbase + NKEYS <= min(ic.kv_end, ic.c_rows))          // uniform: whole tile inside the key range, in pages
             fetch_kv_impl<true>(p, ic, kbase, t);
         else
             fetch_kv_impl<false>(p, ic, kbase, t);
@@ -534,9 +559,15 @@ struct Loader {
             const Row r = row_of(p, ic, kbase, t, ps);
             // wave-uniform LDS offset of the group
             const uint32_t go = __builtin_amdgcn_readfirstlane((ps * NW + (t >> 6)) * G_::GS);
-            if (FULL || r.key0 + ((t & 63) >> 2) % KPW < ic.kv_end) {
+            const int key = r.key0 + ((t & 63) >> 2) % KPW;
+            if (FULL || (key < ic.kv_end && key < ic.c_rows)) {
                 dma16(r.kb, lo, __builtin_amdgcn_readfirstlane(kl) + go);
                 dma16(r.vb, lo, __builtin_amdgcn_readfirstlane(vl) + go);
+            } else if (key < ic.kv_end) {                        // a new token of this call: its packed row
+                const Row n = new_row_of(p, ic, r);
+                const uint32_t nlo = new_lane_off(p, t);
+                dma16(n.kb, nlo, __builtin_amdgcn_readfirstlane(kl) + go);
+                dma16(n.vb, nlo, __builtin_amdgcn_readfirstlane(vl) + go);
             } else {
                 *LDS_PTR(u32x4, kl + go + (t & 63) * 16) = u32x4{0, 0, 0, 0};
                 *LDS_PTR(u32x4, vl + go + (t & 63) * 16) = u32x4{0, 0, 0, 0};
@@ -545,7 +576,7 @@ struct Loader {
     }
     __device__ __forceinline__ void dma(const AttnParams& p, const ItemCtx& ic, int kbase, int t, uint32_t kl,
                                         uint32_t vl) const {
-        if (kbase + NKEYS <= ic.kv_end)
+        if (kbase + NKEYS <= min(ic.kv_end, ic.c_rows))
             dma_impl<true>(p, ic, kbase, t, kl, vl);
         else
             dma_impl<false>(p, ic, kbase, t, kl, vl);
@@ -832,6 +863,35 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
 }
 
 // ---------------------------------------------------------------------------------------------
+// append item (bf16 cache): the page writes of the call, riding in the attention launch.  One item moves nq
+// consecutive packed rows of k_new / v_new, starting with new token q0 of request req and running on into the
+// following requests, to their pages: a bit-exact copy, 16 bytes per thread and step.  The attention items of
+// the same launch never read these page slots (they take new tokens from the packed rows), so the two kinds
+// need no order among themselves.
+
+__device__ __forceinline__ void append_body(const AttnParams& p, const ItemCtx& ic, int D) {
+    const int cpt = p.Hkv * D / 8;                           // 16-byte chunks per packed row (one of K or V)
+    const int cph = D / 8;
+    const int first_row = ic.row_off + ic.q0;                // packed row of the item's first token
+    const int total = ic.nq * cpt;
+    int r = ic.req;                                          // request of the row this thread is at: rows only move forward
+    ReqInfo ri = p.reqs[r];
+    for (int u = threadIdx.x; u < total; u += AWG) {
+        const int row = first_row + u / cpt, rem = u % cpt;
+        while (row >= ri.row_off + ri.L) ri = p.reqs[++r];   // (requests with L = 0 are stepped over)
+        const int h = rem / cph, ch = rem % cph;
+        const int t = ri.C + (row - ri.row_off);
+        const int page = p.block_table[(int64_t)r * p.max_pages + (t >> p.logP)];
+        const int64_t src = ((int64_t)row * p.Hkv + h) * D + ch * 8;
+        const int64_t dst = ((((int64_t)page * p.Hkv + h) << p.logP) + (t & (p.P - 1))) * D + ch * 8;
+        const u32x4 kx = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.k_new) + src * 2);
+        const u32x4 vx = *reinterpret_cast<const u32x4*>(static_cast<const char*>(p.v_new) + src * 2);
+        *reinterpret_cast<u32x4*>(static_cast<char*>(const_cast<void*>(p.k_pool)) + dst * 2) = kx;
+        *reinterpret_cast<u32x4*>(static_cast<char*>(const_cast<void*>(p.v_pool)) + dst * 2) = vx;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
 // the fused attention launch: one workgroup per work item, wide and narrow items in one grid
 
 template <int D, int KVT>
@@ -843,8 +903,10 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
     const ItemCtx ic = load_item(p, blockIdx.x);
     if (kind == KIND_WIDE)
         wide_body<D, KVT>(p, ic, smem);
-    else
+    else if (kind == KIND_NARROW)
         narrow_body<D, KVT>(p, ic, smem);
+    else if (KVT == KV_BF16)
+        append_body(p, ic, D);
 }
 
 // ---------------------------------------------------------------------------------------------

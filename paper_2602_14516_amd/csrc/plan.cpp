@@ -51,9 +51,12 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                     qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_NARROW), 0, L, C + L, L * gn, KIND_NARROW});
                     narrow_keys += C + L;
                 } else {
+                    // A tile that is not full costs its workgroup nearly as much per key as a full one, so the
+                    // remainder of the row goes into the FIRST tile, which sees the fewest keys.
                     const int tq = ATTN_WAVES * tq_wave;
-                    for (int q0 = 0; q0 < L; q0 += tq) {
-                        const int nq = std::min(tq, L - q0);
+                    const int first = L % tq ? L % tq : tq;
+                    for (int q0 = 0; q0 < L; q0 += q0 ? tq : first) {
+                        const int nq = q0 ? tq : first;
                         qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_WIDE), q0, nq, C + q0 + nq, nq * gn, KIND_WIDE});
                         ++n_wide;
                     }
@@ -282,6 +285,20 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
         }
     }
     out.items.swap(sorted);
+
+    // 4b. append items: consecutive runs of packed rows, whatever request they belong to (a decode batch of 96
+    //     rows is two items, not 96); each names the request and token its first row belongs to.
+    if (opt.append_items) {
+        int r = 0;
+        for (int64_t row = 0; row < out.sum_L; row += APPEND_ITEM_ROWS) {
+            while (row >= (int64_t)out.reqs[r].row_off + out.reqs[r].L) ++r;
+            Item it{r, pack_heads(0, 0, 0, KIND_APPEND), (int32_t)(row - out.reqs[r].row_off),
+                    (int32_t)std::min<int64_t>(APPEND_ITEM_ROWS, out.sum_L - row), 0, 0, -1, out.reqs[r].C, out.reqs[r].row_off,
+                    {0, 0, 0}};
+            out.items.push_back(it);
+            ++out.num_append;
+        }
+    }
 
     // 5. byte layout
     out.off_reqs = 0;

@@ -7,6 +7,9 @@
 //                     share K/V tiles staged in LDS (compute-bound prefill work), and
 //   * narrow items -- blocks of at most 32 query rows (decode rows, very short chunks)
 //                     whose 8 waves split the key range (bandwidth-bound work),
+//   * append items -- (bf16 cache, append-then-attend calls) runs of packed new rows to be copied into
+//                     their pages by the same launch; they close the work list, where they fill the CUs
+//                     that run out of attention work first,
 // optionally cutting an item's key range into pieces (split-KV) that a combine pass merges.
 // Workgroup i of a launch runs on accelerator die (XCD) i % 8, each with its own L2, so the
 // launch order also decides which L2 a K/V stream passes through; null items (no work) pad the
@@ -19,7 +22,7 @@
 
 namespace ampd {
 
-enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1, KIND_NULL = 2 };
+enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1, KIND_NULL = 2, KIND_APPEND = 3 };
 
 constexpr int ATTN_WAVES = 8;      // waves of an attention workgroup (one workgroup per CU)
 constexpr int APPEND_MAX_REQS = 128;   // requests per append launch (their lengths travel as kernel arguments)
@@ -58,16 +61,20 @@ struct Shape {
     int Hq, Hkv, D, P;
 };
 
+constexpr int APPEND_ITEM_ROWS = 64;   // packed rows (new tokens, all heads, K and V) that one append item moves
+
 struct PlanOptions {
     int force_kv_splits = 0;
     int wg_slots = 256;   // workgroups resident at once: one per CU
+    bool append_items = false;   // the page writes of the call ride in the attention launch (bf16 cache): append items
+                                 // of APPEND_ITEM_ROWS packed rows each close the work list
 };
 
 struct Plan {
     std::vector<ReqInfo> reqs;
     std::vector<Item> items;
     std::vector<CombItem> combs;
-    int64_t num_wide = 0, num_narrow = 0;
+    int64_t num_wide = 0, num_narrow = 0, num_append = 0;
     int64_t partial_floats = 0;
     int64_t sum_L = 0;
     // byte layout of the device copy: [reqs][items][combs], each 256 B aligned

@@ -68,10 +68,19 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
     items = A.plan_items(c, C, L, mp, force_kv_splits=splits)
     G = Hq // Hkv
     ranges = {}
+    off = np.concatenate([[0], np.cumsum(L)])
+    copied = np.zeros(int(off[-1]), np.int32)          # packed rows moved to their pages by append items
+    seen_append = False
     for req, kind, kvh, g0, gn, q0, nq, kb, ke, po in items.tolist():
         if kind == 2:                                  # null item: pads a die's queue, does no work
             assert req == -1 and nq == 0 and po == -1
             continue
+        if kind == 3:                                  # append item: nq packed rows from token q0 of request req on
+            assert 0 < nq <= 64 and 0 <= q0 < L[req] and po == -1
+            copied[off[req] + q0:off[req] + q0 + nq] += 1
+            seen_append = True
+            continue
+        assert not seen_append, "append items close the work list"
         assert 0 < gn <= 32 and g0 + gn <= G and nq > 0 and kb < ke and kb % 64 == 0
         assert nq * gn <= (256 if kind == 0 else 32)
         for g in range(g0, g0 + gn):
@@ -89,6 +98,7 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
                 assert pos >= vis and rs[-1][0] < vis or len(rs) == 1 or rs[-1][0] < C[r] + L[r]
                 assert pos >= vis
     assert not ranges, "items refer to queries that do not exist"
+    assert np.all(copied == 1), "every new token is written to its page exactly once"
     return items
 
 
@@ -134,6 +144,8 @@ def test_planner_kinds_and_split_policy():
     a = A.plan_items(c, C, L, mp)
     b = A.plan_items(c, C, L, mp)
     assert np.array_equal(a, b)
+    assert info["num_append_items"] == int((a[:, 1] == 3).sum()) == -(-int(L.sum()) // 64) and np.all(a[-info["num_append_items"]:, 1] == 3)
+    a = a[a[:, 1] != 3]
     keys = (a[:, 8] - a[:, 7]).astype(np.int64)
     wide, narrow = a[:, 1] == 0, a[:, 1] == 1
     assert np.all(np.diff(keys[narrow]) <= 0)          # decode items: longest first
@@ -192,6 +204,7 @@ def test_narrow_chunk_policy_small_and_large_launches():
     C = np.full(32, 6000, np.int32)
     L = np.ones(32, np.int32)
     a = A.plan_items(c, C, L, 6001 // 16 + 1)
+    a = a[a[:, 1] != 3]                                 # (the page writes of the 32 new tokens: one append item)
     keys = (a[:, 8] - a[:, 7]).astype(np.int64)
     assert np.all(a[:, 1] == 1)
     assert 2 * 256 <= len(a) <= 3 * 256 and keys.max() <= 4096 and keys.max() % 64 == 0
@@ -199,14 +212,17 @@ def test_narrow_chunk_policy_small_and_large_launches():
     c3 = shape_cache(64, 8, 128, 16)
     C3, L3 = W.config_lengths(3, part="decode")
     a3 = A.plan_items(c3, C3, L3, int(((C3.astype(int) + L3 + 15) // 16).max()))
+    a3 = a3[a3[:, 1] != 3]
     k3 = (a3[:, 8] - a3[:, 7]).astype(np.int64)
     assert k3.max() == 4096 and 7 * 256 <= len(a3) <= 11 * 256
     # twice the rows: the ~8-items-per-CU rule takes over
     a6 = A.plan_items(c3, np.concatenate([C3, C3]), np.concatenate([L3, L3]), int(((C3.astype(int) + L3 + 15) // 16).max()))
+    a6 = a6[a6[:, 1] != 3]
     k6 = (a6[:, 8] - a6[:, 7]).astype(np.int64)
     total = 2 * int((C3.astype(np.int64) + 1).sum()) * 8
     assert k6.max() == -(-(-(-total // 2048)) // 64) * 64 and k6.max() > 4096
     # a tiny launch never goes below 256-key chunks
     a1 = A.plan_items(c, np.full(4, 700, np.int32), np.ones(4, np.int32), 701 // 16 + 1)
+    a1 = a1[a1[:, 1] != 3]
     k1 = (a1[:, 8] - a1[:, 7]).astype(np.int64)
     assert k1.max() == 256 and len(a1) == 4 * 8 * 3
