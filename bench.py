@@ -201,7 +201,7 @@ def model_sweep(torch, A, W):
     res = {"T_pre": [], "T_dec": []}
     sh = W.CONFIG_SHAPES[2]
     for l_hist in (0, 1024, 4096, 16384, 65536):
-        for l_incr in (16, 64, 256, 1024, 4096):
+        for l_incr in (16, 64, 256, 512, 1024, 2048, 4096, 8192):    # (lines are interpolated in log l_incr: factor-2 steps where time grows with it)
             C, L = np.array([l_hist], np.int32), np.array([l_incr], np.int32)
             db = device_batch(torch, A, W, C, L, sh, seed=1)
             fn = make_runner(torch, A, db, "prefill")
@@ -220,6 +220,20 @@ def model_sweep(torch, A, W):
             res["T_dec"].append((b, int(C.sum()), ms * 1e-3))
             del db, fn
             torch.cuda.empty_cache()
+    # T_kv: the GPU halves of a KV transfer (paper Section 3, T_kv(l_ctx; theta_src, theta_dst); Eq. 2): gather l_ctx
+    # tokens of one request from its pages into a packed send buffer, and scatter received rows into pages
+    sh = W.CONFIG_SHAPES[2]
+    res["T_kv"] = []
+    for l_ctx in (256, 1024, 4096, 16384, 65536):
+        T = np.array([l_ctx], np.int32)
+        zero = np.zeros_like(T)
+        db = device_batch(torch, A, W, T, zero, sh, seed=3)
+        kb = torch.empty(l_ctx, sh["Hkv"], sh["d"], dtype=torch.bfloat16, device="cuda")
+        vb = torch.empty_like(kb)
+        t_pack = time_calls(torch, lambda: A.kv_pack(db["cache"], zero, T, db["bt"], 0, sh["Hkv"], kb, vb), 20, 3)
+        t_unpack = time_calls(torch, lambda: A.kv_unpack(db["cache"], zero, T, db["bt"], 0, sh["Hkv"], kb, vb), 20, 3)
+        res["T_kv"].append((l_ctx, t_pack * 1e-3, t_unpack * 1e-3))
+        del db, kb, vb
     from paper_2602_14516_amd.perf_model import fit_alpha_beta_family
     pre = np.array(res["T_pre"], dtype=np.float64)
     fam_p = fit_alpha_beta_family(pre[:, 1], pre[:, 0], pre[:, 2])                 # one line in l_hist per l_incr
@@ -232,7 +246,15 @@ def model_sweep(torch, A, W):
     s3 = W.CONFIG_SHAPES[3]
     xb = decode_bytes(dec[:, 1], dec[:, 0], s3["Hq"], s3["Hkv"], s3["d"])
     md = fit_piecewise_alpha_beta(xb, dec[:, 2], segments=3)
-    return {"only": "model",
+    kvp = np.array(res["T_kv"], dtype=np.float64)
+    fit_pack = fit_piecewise_alpha_beta(kvp[:, 0], kvp[:, 1], segments=1)
+    fit_unpack = fit_piecewise_alpha_beta(kvp[:, 0], kvp[:, 2], segments=1)
+    return {"only": "model", "layer_shapes": {"T_pre": W.CONFIG_SHAPES[2], "T_dec": W.CONFIG_SHAPES[3], "T_kv": W.CONFIG_SHAPES[2]},
+            "T_kv": {"pack": {"alpha_s": float(fit_pack.alpha[0]), "beta_s_per_token": float(fit_pack.beta[0]),
+                              "rel_err_max": float(fit_pack.rel_error(kvp[:, 0], kvp[:, 1]).max())},
+                     "unpack": {"alpha_s": float(fit_unpack.alpha[0]), "beta_s_per_token": float(fit_unpack.beta[0]),
+                                "rel_err_max": float(fit_unpack.rel_error(kvp[:, 0], kvp[:, 2]).max())},
+                     "points_l_ctx_pack_s_unpack_s": [(int(a), float(b_), float(c)) for a, b_, c in res["T_kv"]]},
             "T_pre": {"per_l_incr_lines_in_l_hist": {"l_incr": fam_p.buckets.tolist(), "alpha_s": fam_p.alpha.tolist(),
                                                      "beta_s_per_token": fam_p.beta.tolist(),
                                                      "rel_err_mean": float(err_p.mean()), "rel_err_max": float(err_p.max())},

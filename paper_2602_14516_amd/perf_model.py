@@ -115,3 +115,64 @@ def fit_alpha_beta_family(bucket, size, t) -> AlphaBetaFamily:
         alpha.append(fit.alpha[0])
         beta.append(fit.beta[0])
     return AlphaBetaFamily(bs, np.array(alpha), np.array(beta))
+
+
+# ---------------------------------------------------------------------------------------------------------------------
+# The committed cost model of one MI355X: written by `python -m paper_2602_14516_amd.perf_model <model.json>` from the
+# output of `bench.py --only model`, read by the serving simulator and checked against fresh measurements by the GPU tests.
+
+import json
+import os
+
+COST_MODEL_PATH = os.path.join(os.path.dirname(os.path.abspath(__file__)), "mi355x_cost_model.json")
+# What one GPU cannot measure: the wire between two workers.  One xGMI link of an MI355X moves ~153 GB/s; a transfer
+# between two GPUs uses one link, and a message costs a few microseconds of latency on top.
+LINK_BYTES_PER_S = 153e9
+LINK_LATENCY_S = 10e-6
+
+
+def cost_model_from_sweep(sweep: dict) -> dict:
+    """Constants of the simulator's cost model from the output of `bench.py --only model`: the fitted T_pre and T_dec
+    lines as they are, and T_kv(tokens) = alpha + beta * tokens (one layer) as pack + wire + unpack, the two GPU halves
+    fitted from measured ampd_kv_pack / ampd_kv_unpack times and the wire from the link figures above."""
+    pre, dec, kv = sweep["T_pre"]["per_l_incr_lines_in_l_hist"], sweep["T_dec"]["per_batch_lines_in_sum_ctx"], sweep["T_kv"]
+    sh = sweep["layer_shapes"]["T_kv"]
+    bytes_per_token = 2 * sh["Hkv"] * sh["d"] * 2                      # K and V rows of one token, bf16
+    return {
+        "source": "bench.py --only model on one MI355X; whole C-ABI calls; one attention layer",
+        "layer_shapes": sweep["layer_shapes"],
+        "tpre_l_incr": pre["l_incr"], "tpre_alpha": pre["alpha_s"], "tpre_beta": pre["beta_s_per_token"],
+        "tpre_rel_err": [pre["rel_err_mean"], pre["rel_err_max"]],
+        "tdec_b": dec["b"], "tdec_alpha": dec["alpha_s"], "tdec_beta": dec["beta_s_per_token"],
+        "tdec_rel_err": [dec["rel_err_mean"], dec["rel_err_max"]],
+        "kv_pack": [kv["pack"]["alpha_s"], kv["pack"]["beta_s_per_token"]],
+        "kv_unpack": [kv["unpack"]["alpha_s"], kv["unpack"]["beta_s_per_token"]],
+        "kv_link": [LINK_LATENCY_S, bytes_per_token / LINK_BYTES_PER_S],
+        "kv_alpha": kv["pack"]["alpha_s"] + kv["unpack"]["alpha_s"] + LINK_LATENCY_S,
+        "kv_beta": kv["pack"]["beta_s_per_token"] + kv["unpack"]["beta_s_per_token"] + bytes_per_token / LINK_BYTES_PER_S,
+        "points": {"T_pre": sweep["T_pre"]["points_l_hist_l_incr_seconds"], "T_dec": sweep["T_dec"]["points_b_sum_ctx_seconds"],
+                   "T_kv": kv["points_l_ctx_pack_s_unpack_s"]},
+    }
+
+
+def load_cost_model(path: str = COST_MODEL_PATH) -> dict:
+    with open(path) as f:
+        return json.load(f)
+
+
+def _main(argv):
+    if len(argv) != 2:
+        print("usage: python -m paper_2602_14516_amd.perf_model <output of `bench.py --only model`>")
+        return 2
+    lines = [l for l in open(argv[1]).read().splitlines() if l.startswith("{")]
+    model = cost_model_from_sweep(json.loads(lines[-1]))
+    with open(COST_MODEL_PATH, "w") as f:
+        json.dump(model, f, indent=1)
+        f.write("\n")
+    print("wrote", COST_MODEL_PATH)
+    return 0
+
+
+if __name__ == "__main__":
+    import sys
+    sys.exit(_main(sys.argv))

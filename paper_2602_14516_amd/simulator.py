@@ -42,8 +42,8 @@ class CostModel:
     tdec_b: np.ndarray
     tdec_alpha: np.ndarray
     tdec_beta: np.ndarray
-    kv_alpha: float = 20e-6
-    kv_beta: float = 4096 / 100e9            # bytes of K and V per token and layer / link bandwidth
+    kv_alpha: float = 20e-6                  # per transfer: pack + unpack launches and the link's latency
+    kv_beta: float = 4096 / 100e9            # per token and layer: pack + unpack + bytes of K and V / link bandwidth
     layers: int = 32
     other_s_per_token: float = 0.0
     prefill_speed: float = 1.0               # prefill workers relative to the decode worker's device
@@ -73,16 +73,19 @@ class CostModel:
         return scale(self._tpre, 1.0), scale(self._tpre, self.prefill_speed)
 
 
-# One MI355X, one attention layer, Hq=32 Hkv=8 d=128 (T_pre) and Hq=64 Hkv=8 d=128 (T_dec), bf16 cache: the lines
-# fitted by `bench.py --only model` (whole C-ABI calls: append + attention + combine).
-MI355X_ATTENTION = dict(
-    tpre_l_incr=np.array([16.0, 64.0, 256.0, 1024.0, 4096.0]),
-    tpre_alpha=np.array([31.7e-6, 30.7e-6, 32.1e-6, 48.4e-6, 176.9e-6]),
-    tpre_beta=np.array([1.44e-9, 2.27e-9, 5.14e-9, 16.00e-9, 57.76e-9]),
-    tdec_b=np.array([1.0, 8.0, 32.0, 96.0, 256.0]),
-    tdec_alpha=np.array([20.7e-6, 24.5e-6, 37.0e-6, 56.1e-6, 70.0e-6]),
-    tdec_beta=np.array([2.601e-9, 0.961e-9, 0.682e-9, 0.621e-9, 0.613e-9]),
-)
+# One MI355X, one attention layer (T_pre: Hq=32 Hkv=8 d=128; T_dec: Hq=64 Hkv=8 d=128; bf16 cache): the lines fitted by
+# `bench.py --only model` to whole C-ABI calls, and T_kv as pack + wire + unpack with the two GPU halves fitted from
+# ampd_kv_pack / ampd_kv_unpack timings.  The numbers live in mi355x_cost_model.json, which
+# `python -m paper_2602_14516_amd.perf_model <sweep output>` writes; nothing is typed in by hand.
+def mi355x_attention() -> dict:
+    from .perf_model import load_cost_model
+    m = load_cost_model()
+    return dict(tpre_l_incr=np.array(m["tpre_l_incr"]), tpre_alpha=np.array(m["tpre_alpha"]), tpre_beta=np.array(m["tpre_beta"]),
+                tdec_b=np.array(m["tdec_b"]), tdec_alpha=np.array(m["tdec_alpha"]), tdec_beta=np.array(m["tdec_beta"]),
+                kv_alpha=float(m["kv_alpha"]), kv_beta=float(m["kv_beta"]))
+
+
+MI355X_ATTENTION = mi355x_attention()
 
 
 @dataclass
