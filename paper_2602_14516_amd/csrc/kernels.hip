@@ -308,6 +308,7 @@ __device__ __forceinline__ void static_for(F&& f) {
     }
 }
 
+
 template <int D>
 struct PipeState {
     f32x16 S[2];            // logits of two consecutive blocks (block b lives in S[b & 1])
@@ -469,7 +470,20 @@ struct Loader {
             pg[ps] = key0 < ic.kv_end ? bt[key0 >> p.logP] : 0;
         }
     }
-    static constexpr int DMA_PER_TILE = 2 * NPASS;     // direct loads per wave and tile (K and V)
+    // The same page ids through the vector memory path, for the direct-load pipeline of wide items: lane ps of a
+    // wave fetches the id of the wave's pass ps with one load, and take_pages() moves the ids into scalar registers
+    // once the load has landed.  Scalar loads share their counter with LDS reads and return out of order, so a wave
+    // with page ids in flight has to drain that counter completely at its next fragment read; vector loads retire
+    // in order behind the direct loads of the same step, and the wait that ends the step covers them.
+    int pgv;
+    __device__ __forceinline__ void fetch_pages_v(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
+        const int key0 = kbase + (((t & 63) % NPASS) * NW + (t >> 6)) * KPW;
+        pgv = key0 < ic.kv_end ? ic.bt_row[key0 >> p.logP] : 0;
+    }
+    __device__ __forceinline__ void take_pages() {
+#pragma unroll
+        for (int ps = 0; ps < NPASS; ++ps) pg[ps] = __builtin_amdgcn_readlane(pgv, ps);
+    }
 
     __device__ __forceinline__ static uint32_t lane_off(int t) {
         const int l = t & 63;                          // LDS slot l = (quad, key, chunk in quad)
@@ -625,24 +639,9 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
 }
 
 // ---------------------------------------------------------------------------------------------
-// wide body: 8 waves x 32 query rows share 64-key K/V tiles.
-// bf16 cache: tiles travel global -> LDS directly through a ring of NSTAGE stages, three tiles
-// ahead of the one being consumed, so that ~100 KB per CU are in flight; one barrier per tile.
-// 8-bit cache: register-staged and widened, one tile ahead, two stages.
-
-// Wait until at most `tiles` whole tiles of direct loads are still in flight (they retire in order).
-template <int PER_TILE>
-__device__ __forceinline__ void dma_wait_tiles(int tiles) {
-    if (tiles >= 3)
-        __builtin_amdgcn_s_waitcnt(0x0F70 | ((3 * PER_TILE) & 15) | ((((3 * PER_TILE) >> 4) & 3) << 14));
-    else if (tiles == 2)
-        __builtin_amdgcn_s_waitcnt(0x0F70 | ((2 * PER_TILE) & 15) | ((((2 * PER_TILE) >> 4) & 3) << 14));
-    else if (tiles == 1)
-        __builtin_amdgcn_s_waitcnt(0x0F70 | (PER_TILE & 15) | (((PER_TILE >> 4) & 3) << 14));
-    else
-        __builtin_amdgcn_s_waitcnt(0x0F70);
-    asm volatile("" ::: "memory");
-}
+// wide body: 8 waves x 32 query rows share 128-key K/V stages (two in LDS: one consumed, one being filled).
+// bf16 cache: stages travel global -> LDS directly, issued by one wave of every SIMD; one barrier per stage.
+// 8-bit cache: register-staged and widened on the way into LDS, by all waves.
 
 template <int D, int KVT>
 __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
@@ -679,32 +678,46 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
     PipeState<D> ps;
     // keys from kv_end on (the ragged tail of the last stage) count as masked
     const int lim_eff = min(lim, ic.kv_end - 1);
+    // a wave without rows, or one whose rows all end before this stage, skips it
+    auto computes = [&](int t) { return wave_active && k_lo + t * KT <= w_last; };
     auto compute = [&](int t, uint32_t stage, auto masked) {
         const int kbase = k_lo + t * KT;
-        // a wave without rows, or one whose rows all end before this stage, skips it
-        if (wave_active && kbase <= w_last)
+        if (computes(t))
             stage_pipelined<D, decltype(masked)::value>(stage, stage + G_::KTILE, Q, st, ps, p.c_log2,
                                                         lim_eff - kbase - 4 * (lane >> 5), lane);
     };
     if (DMA) {
-        constexpr int AHEAD = NSTAGE - 1;
-        constexpr int PT = Loader<D, KVT, AWG, KT>::DMA_PER_TILE;
-        static_assert(AHEAD >= 1 && AHEAD <= 3 && 2 * PT < 64, "vmcnt budget");
-        auto issue = [&](int i) {                          // tile i -> stage i % NSTAGE; then page ids of tile i + 1
-            const uint32_t sg = smem + (i % NSTAGE) * G_::WIDE_STAGE;
-            ld.dma(p, ic, k_lo + i * KT, tid, sg, sg + G_::KTILE);
-            if (i + 1 < ntiles) ld.fetch_pages(p, ic, k_lo + (i + 1) * KT, tid);
-        };
-        // whole tiles beyond t+1 that may stay in flight while tile t+1 must have landed
-        auto in_flight_after = [&](int t) { return max(0, min(min(ntiles, t + 1 + AHEAD), nfull) - (t + 2)); };
-        ld.fetch_pages(p, ic, k_lo, tid);
-        for (int i = 0; i < AHEAD && i < ntiles; ++i) issue(i);
-        dma_wait_tiles<PT>(in_flight_after(-1));
+        // Who issues the direct loads.  The CU's memory pipeline takes one 1 KB direct load every ~23 cycles, and a
+        // wave whose load finds the queue full is blocked (instructions issue in order) and computes nothing: when all
+        // eight waves issued their share at the start of a stage, the matrix pipes of all four SIMDs stood still for
+        // the ~1 500 cycles the 64 loads of a stage need, in every stage.  So only one wave of every SIMD loads (waves
+        // w and w + 4 share a SIMD): the four loading waves issue the whole next stage at the start of a stage while
+        // their SIMD partners already compute, and catch up afterwards.  A tile with rows for at most four waves lets
+        // its idle half do the loading.
+        static_assert(NSTAGE == 2, "tile t + 1 is loaded during stage t; the page ids of tile t + 2 travel behind it");
+        constexpr int LW = ATTN_WAVES / 2;
+        using LD = Loader<D, KVT, 64 * LW, KT>;
+        LD ldh;
+        const int n_active = (ic.nq + tqw - 1) / tqw;      // waves that have rows
+        const int lbase = n_active <= LW ? LW : 0;
+        const bool loader = wave >= lbase && wave < lbase + LW;
+        const int lt = tid - lbase * 64;                   // thread index among the loading waves
+        if (loader) {
+            ldh.fetch_pages(p, ic, k_lo, lt);
+            ldh.dma(p, ic, k_lo, lt, smem, smem + G_::KTILE);
+            if (ntiles > 1) ldh.fetch_pages_v(p, ic, k_lo + KT, lt);
+        }
+        dma_wait();
         __syncthreads();
         auto step = [&](int t, auto masked) {
-            if (t + AHEAD < ntiles) issue(t + AHEAD);
+            if (loader && t + 1 < ntiles) {
+                const uint32_t sg = smem + ((t + 1) % NSTAGE) * G_::WIDE_STAGE;
+                ldh.take_pages();                          // (their load was waited for at the end of the previous step)
+                ldh.dma(p, ic, k_lo + (t + 1) * KT, lt, sg, sg + G_::KTILE);
+                if (t + 2 < ntiles) ldh.fetch_pages_v(p, ic, k_lo + (t + 2) * KT, lt);
+            }
             compute(t, smem + (t % NSTAGE) * G_::WIDE_STAGE, masked);
-            dma_wait_tiles<PT>(in_flight_after(t));         // tile t+1 has landed in LDS
+            dma_wait();                                    // tile t+1 and the page ids of tile t+2 have landed
             __syncthreads();
         };
         for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
