@@ -397,12 +397,18 @@ def measure_cfg3(torch, A, W, parts, keep=None):
 
 
 def host_call_ms(A, db, reps=200):
-    """Host time of the planning half of one call (validation + work planning, as ampd_workspace_bytes runs them);
-    the GPU half adds the staging copy of the work list and three launches."""
+    """Host time of the planning half of one call (validation + work planning, as ampd_workspace_bytes runs them):
+    for a batch whose lengths differ from the previous call's, and for a repeated batch (the library keeps the last
+    plan of a thread).  The GPU half adds the staging copy of the work list and two or three launches."""
+    C = [np.ascontiguousarray(db["C"] + i) for i in (0, 1)]
+    t0 = time.perf_counter()
+    for i in range(reps):
+        A.workspace_bytes(db["cache"], C[i & 1], db["L"], db["bt"].shape[1] + 1)
+    fresh = (time.perf_counter() - t0) * 1e3 / reps
     t0 = time.perf_counter()
     for _ in range(reps):
         A.workspace_bytes(db["cache"], db["C"], db["L"], db["bt"].shape[1])
-    return (time.perf_counter() - t0) * 1e3 / reps
+    return {"new_lengths": fresh, "repeated_lengths": (time.perf_counter() - t0) * 1e3 / reps}
 
 
 def sources_sha16():

@@ -304,9 +304,10 @@ ampd_status append_then_attend(const ampd_kv_cache* c, const ampd_batch* b, cons
     if (sumL == 0) return AMPD_OK;
     if (!q || !k_new || !v_new || !out) return AMPD_ERR_INVALID_ARG;
     // check the workspace before anything is enqueued
-    Plan plan;
-    vs = make_plan(c, b, opts, true, plan);
+    const Plan* planp = nullptr;
+    vs = make_plan(c, b, opts, true, &planp);
     if (vs != AMPD_OK) return vs;
+    const Plan& plan = *planp;
     if (use_static) {
         if ((size_t)plan.total_bytes > (size_t)AMPD_STATIC_WORKSPACE_BYTES || (size_t)plan.plan_bytes > SLOT_BYTES)
             return AMPD_ERR_WORKSPACE;
@@ -410,9 +411,10 @@ ampd_status ampd_paged_attn(const ampd_kv_cache* cache, const ampd_batch* batch,
                             void* workspace, size_t workspace_bytes, void* stream, const ampd_plan_options* opts) {
     ampd_status vs = validate(cache, batch, true);
     if (vs != AMPD_OK) return vs;
-    Plan plan;
-    vs = make_plan(cache, batch, opts, false, plan);
+    const Plan* planp = nullptr;
+    vs = make_plan(cache, batch, opts, false, &planp);
     if (vs != AMPD_OK) return vs;
+    const Plan& plan = *planp;
     if (plan.items.empty()) return AMPD_OK;
     if (!q || !out) return AMPD_ERR_INVALID_ARG;
     vs = check_workspace(plan, workspace, workspace_bytes);

@@ -3,6 +3,7 @@
 #include "api_host.h"
 
 #include <cmath>
+#include <vector>
 
 namespace ampd {
 namespace host {
@@ -56,7 +57,24 @@ ampd_status validate(const ampd_kv_cache* c, const ampd_batch* b, bool need_pool
     return AMPD_OK;
 }
 
-ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, Plan& plan) {
+// The last plan built on this thread is kept: a caller sizes its workspace with ampd_workspace_bytes and then issues
+// the call with the same lengths, and a serving loop often repeats a batch shape; both then plan once.
+namespace {
+struct PlanKey {
+    int32_t Hq = 0, Hkv = 0, D = 0, P = 0, splits = 0;
+    bool append_items = false;
+    std::vector<int32_t> ctx, incr;
+    bool operator==(const PlanKey& o) const {
+        return Hq == o.Hq && Hkv == o.Hkv && D == o.D && P == o.P && splits == o.splits && append_items == o.append_items &&
+               ctx == o.ctx && incr == o.incr;
+    }
+};
+thread_local PlanKey t_key;
+thread_local Plan t_plan;
+thread_local bool t_plan_valid = false;
+}  // namespace
+
+ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, const Plan** plan) {
     PlanOptions po;
     po.append_items = with_append && c->kv_dtype == AMPD_KV_BF16;
     if (o) {
@@ -65,9 +83,21 @@ ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_pl
             if (o->reserved[i] != 0) return AMPD_ERR_INVALID_ARG;
         po.force_kv_splits = o->force_kv_splits;
     }
-    Shape s{c->num_q_heads, c->num_kv_heads, c->head_dim, c->page_size};
-    build_plan(s, b->num_reqs, b->h_ctx_len, b->h_incr_len, po, plan);
-    if (plan.partial_floats > 0x7fffffff || plan.items.size() > 0x7fffffffu) return AMPD_ERR_UNSUPPORTED;
+    PlanKey key;
+    key.Hq = c->num_q_heads; key.Hkv = c->num_kv_heads; key.D = c->head_dim; key.P = c->page_size;
+    key.splits = po.force_kv_splits;
+    key.append_items = po.append_items;
+    key.ctx.assign(b->h_ctx_len, b->h_ctx_len + b->num_reqs);
+    key.incr.assign(b->h_incr_len, b->h_incr_len + b->num_reqs);
+    if (!(t_plan_valid && key == t_key)) {
+        t_plan_valid = false;
+        Shape s{c->num_q_heads, c->num_kv_heads, c->head_dim, c->page_size};
+        build_plan(s, b->num_reqs, b->h_ctx_len, b->h_incr_len, po, t_plan);
+        t_key = std::move(key);
+        t_plan_valid = true;
+    }
+    if (t_plan.partial_floats > 0x7fffffff || t_plan.items.size() > 0x7fffffffu) return AMPD_ERR_UNSUPPORTED;
+    *plan = &t_plan;
     return AMPD_OK;
 }
 
@@ -81,9 +111,9 @@ extern "C" {
 
 size_t ampd_workspace_bytes_opts(const ampd_kv_cache* cache, const ampd_batch* batch, const ampd_plan_options* opts) {
     if (validate(cache, batch, false) != AMPD_OK) return 0;
-    Plan plan;
-    if (make_plan(cache, batch, opts, true, plan) != AMPD_OK) return 0;
-    return (size_t)plan.total_bytes;
+    const Plan* plan = nullptr;
+    if (make_plan(cache, batch, opts, true, &plan) != AMPD_OK) return 0;
+    return (size_t)plan->total_bytes;
 }
 
 size_t ampd_workspace_bytes(const ampd_kv_cache* cache, const ampd_batch* batch) {
@@ -95,9 +125,10 @@ ampd_status ampd_plan_describe(const ampd_kv_cache* cache, const ampd_batch* bat
     if (!info) return AMPD_ERR_INVALID_ARG;
     ampd_status vs = validate(cache, batch, false);
     if (vs != AMPD_OK) return vs;
-    Plan plan;
-    vs = make_plan(cache, batch, opts, true, plan);
+    const Plan* planp = nullptr;
+    vs = make_plan(cache, batch, opts, true, &planp);
     if (vs != AMPD_OK) return vs;
+    const Plan& plan = *planp;
     info->num_items = (int64_t)plan.items.size();
     info->num_wide_items = plan.num_wide;
     info->num_narrow_items = plan.num_narrow;
@@ -113,9 +144,10 @@ int64_t ampd_plan_items(const ampd_kv_cache* cache, const ampd_batch* batch, con
                         int32_t* h_items, int64_t max_items) {
     ampd_status vs = validate(cache, batch, false);
     if (vs != AMPD_OK) return vs;
-    Plan plan;
-    vs = make_plan(cache, batch, opts, true, plan);
+    const Plan* planp = nullptr;
+    vs = make_plan(cache, batch, opts, true, &planp);
     if (vs != AMPD_OK) return vs;
+    const Plan& plan = *planp;
     const int64_t n = (int64_t)plan.items.size();
     for (int64_t i = 0; i < n && i < max_items && h_items; ++i) {
         const Item& it = plan.items[i];

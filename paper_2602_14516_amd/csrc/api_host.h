@@ -13,7 +13,8 @@ int log2_exact(int x);                                   // log2 of a power of t
 ampd_status validate(const ampd_kv_cache* c, const ampd_batch* b, bool need_pools);
 // with_append: plan an append-then-attend call; for a bf16 cache the page writes then ride in the attention launch
 // as append items (an 8-bit cache quantises in a launch of its own first)
-ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, Plan& plan);
+// *plan points at a plan owned by the calling thread: valid until that thread's next make_plan
+ampd_status make_plan(const ampd_kv_cache* c, const ampd_batch* b, const ampd_plan_options* o, bool with_append, const Plan** plan);
 
 }  // namespace host
 }  // namespace ampd
