@@ -458,8 +458,10 @@ struct Loader {
     float ks[NPASS], vs[NPASS];
 
     // t: thread index inside the group of NTHR threads.  The block table is read through the
-    // scalar cache (it is constant for the duration of the kernel): scalar loads have their own
-    // counter, so waiting for a page id never waits for K/V data in flight.
+    // scalar cache (it is constant for the duration of the kernel): scalar loads do not count
+    // as vector-memory loads, so waiting for a page id never waits for K/V data in flight.
+    // (They do share a counter with LDS reads: the register-staged paths and the first stage
+    // of a wide item use this variant, the direct-load pipeline uses fetch_pages_v below.)
     __device__ __forceinline__ void fetch_pages(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
         const auto* bt = reinterpret_cast<const __attribute__((address_space(4))) int32_t*>(
             reinterpret_cast<uintptr_t>(ic.bt_row));
