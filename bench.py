@@ -169,19 +169,23 @@ def trace_replay(torch, A, W, max_ticks=None):
     ws_need = max(A.workspace_bytes(cache, t.ctx_len, t.incr_len, tr.block_table.shape[1]) for t in ticks[::16] + [max(ticks, key=lambda x: int(x.incr_len.sum()))])
     ws = torch.empty(4 * ws_need + (1 << 20), dtype=torch.uint8, device="cuda")
     out = torch.empty(max_rows, Hq, d, dtype=torch.bfloat16, device="cuda")
+    # the bookkeeping of the figures and the tensor views are made before the clock starts: a tick of the timed loop is the call alone
     flops = by = 0
-    torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    e0.record()
+    args = []
     for i, t in enumerate(ticks):
         n = int(t.incr_len.sum())
         q = rnd[:n * Hq * d].view(n, Hq, d)
         k = rnd[n * Hq * d:n * (Hq + Hkv) * d].view(n, Hkv, d)
         v = rnd[n * (Hq + Hkv) * d:n * (Hq + 2 * Hkv) * d].view(n, Hkv, d)
-        A.mixed_batch_attn(cache, t.ctx_len, t.incr_len, bts[i], q, k, v, out=out[:n], workspace=ws)
+        args.append((t.ctx_len, t.incr_len, bts[i], q, k, v, out[:n]))
         flops += flops_of(t.ctx_len, t.incr_len, Hq, d)
         by += bytes_of(t.ctx_len, t.incr_len, Hq, Hkv, d, P, kvb=1) + int((2 * 4 * Hkv * ((t.ctx_len.astype(np.int64) + t.incr_len + P - 1) // P)).sum())
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for C, L, bt, q, k, v, o in args:
+        A.mixed_batch_attn(cache, C, L, bt, q, k, v, out=o, workspace=ws)
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
@@ -190,7 +194,45 @@ def trace_replay(torch, A, W, max_ticks=None):
             "pool_pages": tr.num_pages, "kv_dtype": "fp8-e4m3 + fp32 scale per (page, head)",
             "wall_s": wall, "stream_span_s": gpu, "algorithmic_TFLOP": flops / 1e12, "algorithmic_GB": by / 1e9,
             "TFLOPs": flops / wall / 1e12, "GBps": by / wall / 1e9, "calls_per_s": len(ticks) / wall,
-            "note": "one Python-driven C-ABI call per tick (plan, upload, append, attention, combine): at ~100 us per tick the host call path and the four small launches are of the same order"}
+            "note": "one Python-driven C-ABI call per tick (plan, quantising append carrying the work list, attention, combine); the ticks are small, so the host call path and the launches are of the same order"}
+
+
+def data_dependence(torch, A, W, steps=100, warmup=20):
+    """The step of configuration 2 (same work list, same bytes moved, same instructions) on operands of different
+    values: the duration follows the clock that the power management grants, and that depends on how much the operand
+    bits toggle in the matrix pipes."""
+    batch = W.make_config(2)
+    shape = dict(Hq=batch.Hq, Hkv=batch.Hkv, d=batch.d, P=batch.P)
+    db = device_batch(torch, A, W, batch.ctx_len, batch.incr_len, shape, seed=3)
+    step = make_runner(torch, A, db, "prefill")
+    K = (db["cache"].k_pool, db["k_new"])
+    V = (db["cache"].v_pool, db["v_new"])
+    Q = (db["q"],)
+    every = K + V + Q
+    saved = [t.clone() for t in every]
+    out = []
+
+    def run(tag, zero=(), fill=None):
+        for t, s_ in zip(every, saved):
+            t.copy_(s_)
+        for t in zero:
+            t.zero_()
+        if fill is not None:
+            for t in every:
+                t.fill_(fill)
+        ms = time_calls(torch, step, steps, warmup)
+        kt = kernel_times(torch, A, step, 10)
+        out.append({"operands": tag, "ms_per_step": ms, "attn_kernel_ms": float(kt[0]),
+                    "frac_of_bf16_peak": batch.flops() / (kt[0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+
+    run("Q, K, V ~ N(0,1)")
+    run("all zero", zero=every)
+    run("Q = 0", zero=Q)
+    run("K = 0", zero=K)
+    run("V = 0", zero=V)
+    run("all 0.5", fill=0.5)
+    run("Q, K, V ~ N(0,1) again")
+    return {"only": "datadep", "workload": "configuration 2, one step", "runs": out}
 
 
 def model_sweep(torch, A, W):
@@ -445,7 +487,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'decode_fp8' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'simulate' | 'cfg4' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'decode_fp8' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'simulate' | 'cfg4' | 'datadep' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -500,6 +542,9 @@ def main():
         print(json.dumps({"only": "copycal", "bytes_read": x.numel() * 4, "bytes_written": x.numel() * 4}))
         return
 
+    if args.only == "datadep":
+        print(json.dumps(data_dependence(torch, A, W)))
+        return
     if args.only == "cfg4":
         print(json.dumps({"only": "cfg4", **measure_cfg4(torch, A, W)}))
         return

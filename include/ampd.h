@@ -24,8 +24,8 @@
  *     device array of AMPD_STATIC_WORKSPACE_BYTES (see ampd_mixed_batch_attn_static).
  *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the default
  *     stream) and the calls return without waiting for the GPU: a call takes a staging
- *     buffer that no enqueued copy still reads (completion is polled), and when all are
- *     busy it pins one more, so the ring grows to the number of calls the caller keeps in
+ *     buffer that no enqueued copy still reads (the attention launch of a call marks its
+ *     buffer free in a flag word the host polls), and when all are busy it pins one more, so the ring grows to the number of calls the caller keeps in
  *     flight (at 4096 buffers a call waits for the oldest instead).  The one exception is
  *     ampd_mixed_batch_attn_static, which may not allocate and waits for the oldest buffer.
  *   - HOST arrays are read before the call returns and may be reused immediately.

@@ -3,9 +3,11 @@
 // touch a GPU live in api_host.cpp.
 #include <hip/hip_runtime.h>
 
+#include <chrono>
 #include <cmath>
 #include <cstring>
 #include <mutex>
+#include <thread>
 #include <vector>
 
 #include "ampd.h"
@@ -21,9 +23,11 @@ using namespace ampd::host;
 // ---- per-device state: pinned staging ring, static workspace ------------------------------------
 // The work list is built on the host in pinned memory and copied to the workspace by the GPU reading the pinned
 // buffer directly.  Every call takes a ring slot that no enqueued copy still reads: a slot becomes free once the
-// event recorded behind its copy has completed (polled, never waited for).  When every slot is busy the ring grows,
-// so the depth of the ring follows the number of calls the caller keeps in flight; only a call that may not
-// allocate (the static-workspace entry point) waits for the oldest slot instead.
+// attention launch of its call has started, which that launch reports by storing the call's sequence number into a
+// flag word behind the slot (polled, never waited for; no HIP event sits between the launches of a call, where a
+// record costs ~4 us of GPU time per call).  When every slot is busy the ring grows, so the depth of the ring follows
+// the number of calls the caller keeps in flight; only a call that may not allocate (the static-workspace entry
+// point) waits for the oldest slot instead.
 
 // Device memory that the static-workspace entry point uses in place of a caller-provided workspace.  On the host
 // this name is only a handle for hipGetSymbolAddress: the address that kernels and copies take is the one
@@ -33,7 +37,8 @@ static __device__ __align__(256) unsigned char g_static_workspace[AMPD_STATIC_WO
 struct Slot {
     void* host = nullptr;
     size_t cap = 0;
-    hipEvent_t ev = nullptr;
+    uint32_t* flag = nullptr;          // in the same pinned allocation, behind the cap bytes; written by the GPU
+    uint32_t seq = 0;                  // value the flag takes once the slot is free again
     bool pending = false;
 };
 struct DeviceState {
@@ -41,9 +46,11 @@ struct DeviceState {
     void* static_ws = nullptr;         // device address of g_static_workspace on this device
     std::vector<Slot> ring;
     size_t next = 0;
+    uint32_t seq = 0;                  // sequence number of the last call that took a slot
 };
 constexpr int MAX_DEVICES = 64;
 constexpr size_t SLOT_BYTES = 256u << 10;      // ~5 000 work items; larger plans get a slot of their own size
+constexpr size_t FLAG_BYTES = 256;
 constexpr size_t RING_INITIAL = 32;
 constexpr size_t RING_MAX = 4096;              // beyond this many calls in flight a call waits for the oldest
 std::mutex g_mu;
@@ -56,16 +63,17 @@ thread_local bool t_valid = false, t_has_append = false;
 hipError_t new_slot(size_t bytes, Slot* s) {
     size_t cap = SLOT_BYTES;
     while (cap < bytes) cap <<= 1;
-    hipError_t e = hipHostMalloc(&s->host, cap, hipHostMallocDefault);
+    // coherent (fine-grained) host memory: the GPU's store to the flag must become visible while later work still runs
+    const hipError_t e = hipHostMalloc(&s->host, cap + FLAG_BYTES, hipHostMallocCoherent);
     if (e != hipSuccess) return e;
     s->cap = cap;
-    e = hipEventCreateWithFlags(&s->ev, hipEventDisableTiming);
-    if (e != hipSuccess) {
-        (void)hipHostFree(s->host);
-        *s = Slot();
-    }
-    return e;
+    s->flag = reinterpret_cast<uint32_t*>(static_cast<char*>(s->host) + cap);
+    *s->flag = 0;
+    s->seq = 0;
+    return hipSuccess;
 }
+
+bool slot_released(const Slot& s) { return __atomic_load_n(s.flag, __ATOMIC_ACQUIRE) == s.seq; }
 
 // Set-up of the device that is current on the calling thread (g_mu held): resolve the static workspace and pin the
 // initial ring.  Runs once per device.
@@ -100,9 +108,7 @@ hipError_t take_slot(DeviceState& d, size_t bytes, bool may_allocate, Slot** out
         Slot& s = d.ring[(d.next + k) % n];
         if (s.cap < bytes) continue;
         if (s.pending) {
-            const hipError_t q = hipEventQuery(s.ev);
-            if (q == hipErrorNotReady) continue;
-            if (q != hipSuccess) return q;
+            if (!slot_released(s)) continue;
             s.pending = false;
         }
         d.next = (d.next + k + 1) % n;
@@ -120,8 +126,17 @@ hipError_t take_slot(DeviceState& d, size_t bytes, bool may_allocate, Slot** out
     for (size_t k = 0; k < n; ++k) {                   // no allocation allowed (or the ring is at its cap): wait
         Slot& s = d.ring[(d.next + k) % n];
         if (s.cap < bytes) continue;
-        const hipError_t e = hipEventSynchronize(s.ev);
-        if (e != hipSuccess) return e;
+        // for the oldest slot's launch to start; if that takes seconds, for the device: a flag still unset after that
+        // belongs to a call whose attention launch was never made (its enqueue failed)
+        const auto t0 = std::chrono::steady_clock::now();
+        while (!slot_released(s)) {
+            std::this_thread::yield();
+            if (std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+                const hipError_t e = hipDeviceSynchronize();
+                if (e != hipSuccess) return e;
+                break;
+            }
+        }
         s.pending = false;
         d.next = (d.next + k + 1) % n;
         *out = &s;
@@ -206,7 +221,7 @@ ampd_status check_workspace(const Plan& plan, const void* workspace, size_t work
 }
 
 // Stage the work list in a pinned ring slot of the current device (the caller holds g_mu and, once the launch that
-// reads the slot is enqueued, records the slot's event and marks it pending).
+// reads the slot is enqueued, gives the slot its sequence number and marks it pending).
 ampd_status stage_plan(DeviceState& d, const Plan& plan, void* workspace, bool may_allocate, Slot** slot, PendingUpload* up) {
     HIP_TRY(take_slot(d, (size_t)plan.plan_bytes, may_allocate, slot));
     char* h = static_cast<char*>((*slot)->host);
@@ -230,6 +245,8 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     // bf16 cache: the page writes are append items of the attention launch (the plan holds them), and the attention
     // items read the new tokens from k_new / v_new; 8-bit cache: a quantising append launch goes first
     const bool fused_append = k_new && plan.num_append > 0;
+    uint32_t* slot_flag = nullptr;     // the attention launch below releases the staging slot through these
+    uint32_t slot_seq = 0;
 
     {
         std::lock_guard<std::mutex> lk(g_mu);
@@ -252,8 +269,10 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
             if (vs != AMPD_OK) return vs;
         }
         if (up.bytes > 0) HIP_TRY(launch_upload(up.src, up.dst, up.bytes, st));
-        HIP_TRY(hipEventRecord(s->ev, st));
+        s->seq = ++d->seq;
         s->pending = true;
+        slot_flag = s->flag;
+        slot_seq = s->seq;
     }
 
     char* ws = static_cast<char*>(workspace);
@@ -278,14 +297,19 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     p.logP = log2_exact(c->page_size);
     p.max_pages = b->max_pages_per_req;
     p.c_log2 = c->softmax_scale * 1.44269504088896340736f;
+    p.slot_flag = slot_flag;
+    p.slot_seq = slot_seq;
     const int kvt = c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16;
 
     if (timing) HIP_TRY(hipEventRecord(t_ev[1], st));
     HIP_TRY(launch_attn(p, c->head_dim, kvt, (int)plan.items.size(), st));
     if (timing) HIP_TRY(hipEventRecord(t_ev[2], st));
-    int comb_rows = 0;
-    for (const CombItem& ci : plan.combs) comb_rows = std::max(comb_rows, ci.nq * ((ci.heads >> 16) & 0xff));
-    HIP_TRY(launch_combine(p, c->head_dim, (int)plan.combs.size(), comb_rows, st));
+    int comb_rows = 0, comb_splits = 0;
+    for (const CombItem& ci : plan.combs) {
+        comb_rows = std::max(comb_rows, ci.nq * ((ci.heads >> 16) & 0xff));
+        comb_splits = std::max(comb_splits, (int)ci.nsplit);
+    }
+    HIP_TRY(launch_combine(p, c->head_dim, (int)plan.combs.size(), comb_rows, comb_splits, st));
     if (timing) {
         HIP_TRY(hipEventRecord(t_ev[3], st));
         t_valid = true;

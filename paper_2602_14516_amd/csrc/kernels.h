@@ -25,6 +25,10 @@ struct AttnParams {
     float* partial;
     int32_t Hq, Hkv, P, logP, max_pages;
     float c_log2;              // softmax_scale * log2(e)
+    // The host's pinned staging slot this call's work list came from may be reused once this launch runs (every copy
+    // out of the slot precedes it in stream order): the first workgroup stores slot_seq to *slot_flag (pinned host memory).
+    uint32_t* slot_flag;
+    uint32_t slot_seq;
 };
 
 struct AppendParams {
@@ -49,7 +53,7 @@ struct AppendParams {
 hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream_t st);
 hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st);
 // max_rows: the largest nq * heads among the split tiles (sizes the second grid dimension)
-hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, hipStream_t st);
+hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, int max_splits, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);
 // bf16 only: pack = pages -> packed rows (k_new / v_new are written), otherwise packed rows -> pages
 hipError_t launch_kv_move(const AppendParams& p, bool pack, int max_pages_touched, int nreq, hipStream_t st);

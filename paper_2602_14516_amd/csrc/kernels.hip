@@ -913,6 +913,8 @@ template <int D, int KVT>
 __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
     __shared__ __attribute__((aligned(16))) char smem_raw[Geo<D>::SMEM];
     const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && p.slot_flag)   // releases the host's staging slot (see AttnParams)
+        __hip_atomic_store(p.slot_flag, p.slot_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     const int kind = (p.items[blockIdx.x].heads >> 24) & 0xff;
     if (kind == KIND_NULL) return;                         // a filler that keeps the following items on their XCD
     const ItemCtx ic = load_item(p, blockIdx.x);
@@ -928,23 +930,25 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
 // combine: merge the split-KV partials of one query tile
 //   m = max_s m_s;  l = sum_s l_s 2^(m_s - m);  O = sum_s O_s 2^(m_s - m) / l
 
-constexpr int COMB_ROWS = 16;          // query rows per combine workgroup
+constexpr int COMB_ROWS = 16;          // query rows per combine workgroup when a tile has few splits
+constexpr int COMB_ROWS_SLICED = 2;    // ... and when it has many: the workgroup's threads then share the splits
 
-// One output quad (4 consecutive d of one row) merged over all splits, UN splits at a time: all loads of a group are
-// issued before any is used, so a thread pays one memory latency per UN splits, and the maximum is carried along
-// (acc and l are rescaled when a group raises it) instead of being taken in a pass of its own.
+// One output quad (4 consecutive d of one row) merged over the splits s_begin, s_begin + s_step, ... < nsplit, UN splits
+// at a time: all loads of a group are issued before any is used, so a thread pays one memory latency per UN splits,
+// and the maximum is carried along (acc and l are rescaled when a group raises it) instead of being taken in a pass
+// of its own.  Returns the running maximum (-inf when the thread had no split).
 template <int D, int UN>
-__device__ __forceinline__ void combine_quad(const float* part0, int nsplit, int64_t stride, int64_t ml_off, int64_t o_off,
-                                             f32x4& acc, float& lsum) {
+__device__ __forceinline__ float combine_quad(const float* part0, int nsplit, int s_begin, int s_step, int64_t stride,
+                                              int64_t ml_off, int64_t o_off, f32x4& acc, float& lsum) {
     float m_run = NEG_INF;
     lsum = 0.0f;
     acc = f32x4{0, 0, 0, 0};
-    for (int s0 = 0; s0 < nsplit; s0 += UN) {
+    for (int s0 = s_begin; s0 < nsplit; s0 += UN * s_step) {
         float mv[UN], lv[UN];
         f32x4 ov[UN];
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
-            const int sp = min(s0 + j, nsplit - 1);                  // the tail re-reads the last split and drops it below
+            const int sp = min(s0 + j * s_step, nsplit - 1);         // the tail re-reads the last split and drops it below
             const float* base = part0 + (int64_t)sp * stride;
             mv[j] = base[ml_off];
             lv[j] = base[ml_off + 1];
@@ -959,7 +963,7 @@ __device__ __forceinline__ void combine_quad(const float* part0, int nsplit, int
         acc *= back;
 #pragma unroll
         for (int j = 0; j < UN; ++j) {
-            if (s0 + j < nsplit) {
+            if (s0 + j * s_step < nsplit) {
                 const float w = fast_exp2(mv[j] - muse);
                 lsum += lv[j] * w;
                 acc += ov[j] * w;
@@ -967,34 +971,77 @@ __device__ __forceinline__ void combine_quad(const float* part0, int nsplit, int
         }
         m_run = mg;
     }
+    return m_run;
 }
 
-template <int D>
+// CR query rows per workgroup.  CR * D / 4 output quads; when that is less than the workgroup, its WG / (CR * D / 4)
+// thread slices each take every NSL-th split of a quad and slice 0 merges their results through LDS: a tile with a
+// hundred splits and few rows (a decode row over a long context) is then a chain of one or two memory latencies per
+// thread instead of eight, on NSL times as many workgroups.
+template <int D, int CR>
 __global__ __launch_bounds__(WG) void combine_kernel(const AttnParams p) {
+    constexpr int QPR = D / 4;                         // float4 groups per row
+    constexpr int NSL = CR * QPR >= WG ? 1 : WG / (CR * QPR);
+    constexpr int PER = CR * QPR < WG ? CR * QPR : WG; // (row, quad) pairs in flight per pass
+    __shared__ float red[NSL > 1 ? (NSL - 1) * PER * 6 : 1];
     const CombItem ci = p.combs[blockIdx.x];
     const int kvh = ci.heads & 0xff, g0 = (ci.heads >> 8) & 0xff, gn = (ci.heads >> 16) & 0xff;
     const int rows = ci.nq * gn;
-    const int r0 = blockIdx.y * COMB_ROWS;                  // grid.y covers the tallest tile (256 rows)
+    const int r0 = blockIdx.y * CR;                    // grid.y covers the tallest tile
     if (r0 >= rows) return;
     const ReqInfo ri = p.reqs[ci.req];
-    const int nr = min(COMB_ROWS, rows - r0);
-    constexpr int QPR = D / 4;                         // float4 groups per row
-    for (int u = threadIdx.x; u < nr * QPR; u += WG) {
-        const int r = r0 + u / QPR, dq = (u % QPR) * 4;
-        const float* part0 = p.partial + ci.part_off;
-        const int64_t ml_off = (int64_t)rows * D + r * 2;
-        float lsum;
-        f32x4 acc;
-        if (ci.nsplit > 8)                                  // long decode contexts: a hundred splits and more
-            combine_quad<D, 16>(part0, ci.nsplit, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
-        else
-            combine_quad<D, 4>(part0, ci.nsplit, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
+    const int nr = min(CR, rows - r0);
+    const int slice = threadIdx.x / PER, u0 = threadIdx.x % PER;
+    const float* part0 = p.partial + ci.part_off;
+    auto finish = [&](int r, int dq, const f32x4& acc, float lsum) {
         const float inv = 1.0f / lsum;
         const int tl = r / gn, hg = r - tl * gn;
         const int hq = kvh * (p.Hq / p.Hkv) + g0 + hg;
         char* dst = static_cast<char*>(p.out) + (((int64_t)(ri.row_off + ci.q0 + tl) * p.Hq + hq) * D + dq) * 2;
         bf16x4 o = {(__bf16)(acc[0] * inv), (__bf16)(acc[1] * inv), (__bf16)(acc[2] * inv), (__bf16)(acc[3] * inv)};
         *reinterpret_cast<u32x2*>(dst) = __builtin_bit_cast(u32x2, o);
+    };
+    if constexpr (NSL == 1) {
+        for (int u = u0; u < nr * QPR; u += PER) {
+            const int r = r0 + u / QPR, dq = (u % QPR) * 4;
+            const int64_t ml_off = (int64_t)rows * D + r * 2;
+            float lsum;
+            f32x4 acc;
+            if (ci.nsplit > 8)
+                combine_quad<D, 16>(part0, ci.nsplit, 0, 1, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
+            else
+                combine_quad<D, 4>(part0, ci.nsplit, 0, 1, ci.part_stride, ml_off, (int64_t)r * D + dq, acc, lsum);
+            finish(r, dq, acc, lsum);
+        }
+    } else {
+        const bool active = u0 < nr * QPR;             // one pass: nr * QPR <= PER
+        const int r = r0 + u0 / QPR, dq = (u0 % QPR) * 4;
+        float lsum = 0.0f, m = NEG_INF;
+        f32x4 acc = {0, 0, 0, 0};
+        if (active)
+            m = combine_quad<D, 16>(part0, ci.nsplit, slice, NSL, ci.part_stride, (int64_t)rows * D + r * 2,
+                                    (int64_t)r * D + dq, acc, lsum);
+        if (active && slice > 0) {
+            float* w = red + ((slice - 1) * PER + u0) * 6;
+            w[0] = m; w[1] = lsum; w[2] = acc[0]; w[3] = acc[1]; w[4] = acc[2]; w[5] = acc[3];
+        }
+        __syncthreads();
+        if (!active || slice > 0) return;
+        float mall = m;
+#pragma unroll
+        for (int s = 1; s < NSL; ++s) mall = fmaxf(mall, red[((s - 1) * PER + u0) * 6]);
+        const float muse = mall == NEG_INF ? 0.0f : mall;
+        const float w0 = fast_exp2(m - muse);
+        lsum *= w0;
+        acc *= w0;
+#pragma unroll
+        for (int s = 1; s < NSL; ++s) {
+            const float* rd = red + ((s - 1) * PER + u0) * 6;
+            const float w = fast_exp2(rd[0] - muse);
+            lsum += rd[1] * w;
+            acc += f32x4{rd[2], rd[3], rd[4], rd[5]} * w;
+        }
+        finish(r, dq, acc, lsum);
     }
 }
 
@@ -1180,13 +1227,24 @@ hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStrea
     return hipErrorInvalidValue;
 }
 
-hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, hipStream_t st) {
+// max_rows: rows of the tallest tile; max_splits: splits of the most finely split one
+hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, int max_splits, hipStream_t st) {
     if (ncombs <= 0) return hipSuccess;
-    const dim3 grid(ncombs, (max_rows + COMB_ROWS - 1) / COMB_ROWS);
-    if (D == 128)
-        hipLaunchKernelGGL((combine_kernel<128>), grid, dim3(WG), 0, st, p);
-    else
-        hipLaunchKernelGGL((combine_kernel<64>), grid, dim3(WG), 0, st, p);
+    // many splits and a launch that would otherwise leave most of the chip idle: let thread slices share the splits
+    const bool sliced = max_splits > 16 && (int64_t)ncombs * ((max_rows + COMB_ROWS - 1) / COMB_ROWS) < 512;
+    const int cr = sliced ? COMB_ROWS_SLICED : COMB_ROWS;
+    const dim3 grid(ncombs, (max_rows + cr - 1) / cr);
+    if (D == 128) {
+        if (sliced)
+            hipLaunchKernelGGL((combine_kernel<128, COMB_ROWS_SLICED>), grid, dim3(WG), 0, st, p);
+        else
+            hipLaunchKernelGGL((combine_kernel<128, COMB_ROWS>), grid, dim3(WG), 0, st, p);
+    } else {
+        if (sliced)
+            hipLaunchKernelGGL((combine_kernel<64, COMB_ROWS_SLICED>), grid, dim3(WG), 0, st, p);
+        else
+            hipLaunchKernelGGL((combine_kernel<64, COMB_ROWS>), grid, dim3(WG), 0, st, p);
+    }
     return hipGetLastError();
 }
 

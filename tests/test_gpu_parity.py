@@ -100,6 +100,16 @@ def test_many_kv_splits_take_the_wide_combine_groups(splits):
     compare(b, out, label=f"splits{splits}")
 
 
+@pytest.mark.parametrize("d,G", [(64, 3), (128, 5)])
+def test_many_kv_splits_odd_row_counts(d, G):
+    """Few tiles with many splits are combined by thread slices that share a tile's splits (two rows per workgroup):
+    odd row counts (3 or 5 heads per KV head) leave the last workgroup of a tile one row, and d = 64 doubles the slices."""
+    print(f"case: many splits, odd rows, d={d} G={G}", flush=True)
+    b = W.make_batch([9000, 4100, 700], [1, 5, 1], 2 * G, 2, d, 16, seed=29, poison=True)
+    out = run_attn(DevBatch(b), force_kv_splits=40)
+    compare(b, out, label=f"splits40 d{d} G{G}")
+
+
 def test_mixed_equals_separate_sub_batches():
     print("case: mixed vs separate", flush=True)
     C = [700, 90, 2048, 5, 300, 1500]
