@@ -186,13 +186,14 @@ def trace_replay(torch, A, W, max_ticks=None):
     e0.record()
     for C, L, bt, q, k, v, o in args:
         A.mixed_batch_attn(cache, C, L, bt, q, k, v, out=o, workspace=ws)
+    enq = time.perf_counter() - t0                               # the host has enqueued everything
     e1.record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     gpu = e0.elapsed_time(e1) * 1e-3
     return {"ticks": len(ticks), "sessions": tr.num_sessions, "tokens_appended": int(sum(int(t.incr_len.sum()) for t in ticks)),
             "pool_pages": tr.num_pages, "kv_dtype": "fp8-e4m3 + fp32 scale per (page, head)",
-            "wall_s": wall, "stream_span_s": gpu, "algorithmic_TFLOP": flops / 1e12, "algorithmic_GB": by / 1e9,
+            "wall_s": wall, "host_enqueue_s": enq, "stream_span_s": gpu, "algorithmic_TFLOP": flops / 1e12, "algorithmic_GB": by / 1e9,
             "TFLOPs": flops / wall / 1e12, "GBps": by / wall / 1e9, "calls_per_s": len(ticks) / wall,
             "note": "one Python-driven C-ABI call per tick (plan, quantising append carrying the work list, attention, combine); the ticks are small, so the host call path and the launches are of the same order"}
 

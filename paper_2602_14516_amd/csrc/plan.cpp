@@ -2,6 +2,7 @@
 #include "plan.h"
 
 #include <algorithm>
+#include <utility>
 
 namespace ampd {
 
@@ -9,7 +10,7 @@ namespace {
 
 constexpr int KV_TILE = 64;          // keys per LDS tile of a wide item; split points are multiples of it
 constexpr int MIN_NARROW_CHUNK = 256;
-constexpr int NARROW_FAT_CHUNK = 4096;
+constexpr int NARROW_ITEM_KEYS = 512;  // fixed cost of a narrow item (item, Q, page ids, first block, merge), in keys streamed
 constexpr int MIN_WIDE_CHUNK = 1024;
 constexpr int NUM_XCD = 8;            // accelerator dies; workgroup i is dispatched to die i % NUM_XCD
 
@@ -39,6 +40,7 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
     std::vector<QBlock> qb;
     int64_t narrow_keys = 0;
     int64_t n_wide = 0;
+    std::vector<std::pair<int32_t, int32_t>> narrow_runs;   // (keys, number of consecutive narrow blocks with that many)
     for (int r = 0; r < num_reqs; ++r) {
         const int C = ctx_len[r], L = incr_len[r];
         if (L <= 0) continue;
@@ -50,6 +52,10 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                 if ((int64_t)L * gn <= 32) {
                     qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_NARROW), 0, L, C + L, L * gn, KIND_NARROW});
                     narrow_keys += C + L;
+                    if (!narrow_runs.empty() && narrow_runs.back().first == C + L)
+                        ++narrow_runs.back().second;
+                    else
+                        narrow_runs.emplace_back(C + L, 1);
                 } else {
                     // A tile that is not full costs its workgroup nearly as much per key as a full one, so the
                     // remainder of the row goes into the FIRST tile, which sees the fewest keys.
@@ -69,12 +75,51 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
     int64_t narrow_chunk = 1 << 30, wide_chunk = 1 << 30;
     if (opt.force_kv_splits <= 0) {
         if (narrow_keys > 0) {
-            // ~8 items per resident workgroup slot keep the tail short, but an item costs a few microseconds
-            // before its first key arrives (item, Q, page ids, first block), about as long as streaming 100 KB:
-            // small launches therefore take chunks of up to NARROW_FAT_CHUNK keys as long as ~2 items per slot remain
-            const int64_t fine = ceil_div(narrow_keys, 8 * (int64_t)opt.wg_slots);
-            const int64_t coarse = ceil_div(narrow_keys, 2 * (int64_t)opt.wg_slots);
-            narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(std::min(coarse, std::max<int64_t>(NARROW_FAT_CHUNK, fine)), KV_TILE));
+            // An item costs a few microseconds before its first key arrives and after its last (item, Q, page ids,
+            // first block; merge of the waves), and a CU runs one item at a time, so nothing hides that: few, long items
+            // win as long as the slots (resident workgroups) stay evenly loaded.
+            //  - Two or more rows per slot: whole rows balance well by themselves (longest first); only a row longer
+            //    than a slot's share of the keys is cut.
+            //  - Fewer: candidates are the smallest chunk whose items fit one round on the slots (p = 1) and the
+            //    chunks that give ~p items per slot, p = 2, 3, 4.  One round lasts as long as its longest piece; several
+            //    rounds about a slot's share of the keys plus half a longest piece; every item adds its fixed cost.
+            const int64_t slots = opt.wg_slots;
+            auto count_items = [&](int64_t chunk) {
+                int64_t n = 0;
+                for (const auto& r : narrow_runs) n += ceil_div(r.first, chunk) * r.second;
+                return n;
+            };
+            int64_t n_blocks = 0, max_len = 0;
+            for (const auto& r : narrow_runs) {
+                n_blocks += r.second;
+                max_len = std::max<int64_t>(max_len, r.first);
+            }
+            const int64_t base = ceil_div(narrow_keys, slots);
+            if (n_blocks >= 2 * slots) {
+                narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(base, KV_TILE));
+            } else {
+                int64_t best_cost = -1;
+                for (int per_slot = 1; per_slot <= 4; ++per_slot) {
+                    int64_t chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(ceil_div(base, per_slot), KV_TILE));
+                    if (per_slot == 1 && n_blocks <= slots && count_items(chunk) > slots) {
+                        int64_t lo = chunk / KV_TILE, hi = ceil_div(max_len, KV_TILE);      // count(hi) = n_blocks <= slots
+                        while (lo + 1 < hi) {
+                            const int64_t mid = (lo + hi) / 2;
+                            (count_items(mid * KV_TILE) > slots ? lo : hi) = mid;
+                        }
+                        chunk = hi * KV_TILE;
+                    }
+                    const int64_t n = count_items(chunk);
+                    const int64_t piece = std::min(chunk, max_len);
+                    const int64_t cost = n <= slots ? piece + NARROW_ITEM_KEYS
+                                                    : base + piece / 2 + ceil_div(NARROW_ITEM_KEYS * n, slots);
+                    if (best_cost < 0 || cost < best_cost) {
+                        best_cost = cost;
+                        narrow_chunk = chunk;
+                    }
+                    if (chunk == MIN_NARROW_CHUNK) break;          // (smaller chunks are not allowed)
+                }
+            }
         }
         if (n_wide > 0 && n_wide < 2 * (int64_t)opt.wg_slots) {
             int64_t max_keys = 0;

@@ -135,9 +135,9 @@ def test_planner_kinds_and_split_policy():
     C, L = W.config_lengths(3)
     mp = int(((C.astype(int) + L + 15) // 16).max())
     info = A.plan_describe(c, C, L, mp)
-    # decode rows x 8 KV heads are narrow and (all but the shortest) split; prefill rows are wide and unsplit
-    assert 0.6 * 96 * 8 < info["num_combine_items"] <= 96 * 8
-    assert info["num_narrow_items"] > 2 * 96 * 8 - 100
+    # decode rows x 8 KV heads are narrow: 768 blocks for 256 workgroup slots, so none is cut; prefill rows are wide and unsplit
+    assert info["num_combine_items"] == 0
+    assert info["num_narrow_items"] == 96 * 8
     assert info["num_wide_items"] == sum(8 * -(-int(l) // 32) for l in L if l > 1)
     assert A.workspace_bytes(c, C, L, mp) == info["plan_bytes"] + -(-info["partial_bytes"] // 256) * 256
     # the order of the work list depends on lengths only (needed for bitwise page-permutation invariance)
@@ -153,6 +153,41 @@ def test_planner_kinds_and_split_policy():
     for part_w, part_n in zip(np.array_split(wide, 4), np.array_split(narrow, 4)):
         assert part_w.any() and part_n.any()
     check_xcd_queues(a, 0.98)
+
+
+def test_planner_narrow_chunks_follow_the_number_of_workgroup_slots():
+    """Decode rows are cut along the keys into few, long items: one round of items on the 256 workgroup slots when the
+    rows are few and long, and several pieces per row when whole rows would fill the slots
+    unevenly (320 rows on 256 slots would take two rounds of whole rows; three pieces each take four rounds of thirds)."""
+    c4 = shape_cache(8, 1, 128, 32)
+    C = np.array([57000, 60000, 50000, 61000], np.int32)
+    L = np.ones(4, np.int32)
+    info = A.plan_describe(c4, C, L, 2000)
+    assert 200 <= info["num_narrow_items"] <= 256 and info["num_combine_items"] == 4
+    a = A.plan_items(c4, C, L, 2000)
+    a = a[a[:, 1] == 1]
+    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
+    for r in range(4):
+        k = keys[a[:, 0] == r]
+        assert k.sum() == C[r] + 1 and (np.sort(k)[1:] == k.max()).all()    # chunk-sized pieces and one remainder
+    c2 = shape_cache(32, 8, 128, 16)
+    C = np.full(40, 10000, np.int32)
+    L = np.ones(40, np.int32)
+    info = A.plan_describe(c2, C, L, 700)
+    assert info["num_combine_items"] == 320 and info["num_narrow_items"] in (3 * 320, 4 * 320)
+    # a small decode batch of uneven rows (208 on 256 slots): one round would last as long as its longest rows, so
+    # the rows are cut for two to three items per slot
+    C = np.random.default_rng(0).integers(500, 8000, 26).astype(np.int32)
+    info = A.plan_describe(c2, C, np.ones(26, np.int32), 700)
+    assert 2 * 256 <= info["num_narrow_items"] <= 3 * 256
+    # ... and of few rows: one round
+    info = A.plan_describe(c2, C[:6], np.ones(6, np.int32), 700)
+    assert 200 <= info["num_narrow_items"] <= 256
+    # a tiny launch never goes below 256-key chunks
+    a1 = A.plan_items(c2, np.full(4, 700, np.int32), np.ones(4, np.int32), 701 // 16 + 1)
+    a1 = a1[a1[:, 1] != 3]
+    k1 = (a1[:, 8] - a1[:, 7]).astype(np.int64)
+    assert k1.max() == 256 and len(a1) == 4 * 8 * 3
 
 
 def check_xcd_queues(a, min_balance):
@@ -196,33 +231,3 @@ def test_planner_spreads_few_streams_over_all_dies():
         assert counts.min() >= 8
 
 
-def test_narrow_chunk_policy_small_and_large_launches():
-    """Decode rows: ~8 items per CU in a large launch; a small launch takes fatter chunks (an item costs a few
-    microseconds before its first key arrives) but keeps about two items per CU."""
-    c = shape_cache(32, 8, 128, 16)
-    # a 32-row decode tick over 6000-token contexts: 1.5 M keys
-    C = np.full(32, 6000, np.int32)
-    L = np.ones(32, np.int32)
-    a = A.plan_items(c, C, L, 6001 // 16 + 1)
-    a = a[a[:, 1] != 3]                                 # (the page writes of the 32 new tokens: one append item)
-    keys = (a[:, 8] - a[:, 7]).astype(np.int64)
-    assert np.all(a[:, 1] == 1)
-    assert 2 * 256 <= len(a) <= 3 * 256 and keys.max() <= 4096 and keys.max() % 64 == 0
-    # the decode rows of configuration 3: 7 M keys; keys / (8 x 256) = 3.5 k is below the 4096 of a small launch
-    c3 = shape_cache(64, 8, 128, 16)
-    C3, L3 = W.config_lengths(3, part="decode")
-    a3 = A.plan_items(c3, C3, L3, int(((C3.astype(int) + L3 + 15) // 16).max()))
-    a3 = a3[a3[:, 1] != 3]
-    k3 = (a3[:, 8] - a3[:, 7]).astype(np.int64)
-    assert k3.max() == 4096 and 7 * 256 <= len(a3) <= 11 * 256
-    # twice the rows: the ~8-items-per-CU rule takes over
-    a6 = A.plan_items(c3, np.concatenate([C3, C3]), np.concatenate([L3, L3]), int(((C3.astype(int) + L3 + 15) // 16).max()))
-    a6 = a6[a6[:, 1] != 3]
-    k6 = (a6[:, 8] - a6[:, 7]).astype(np.int64)
-    total = 2 * int((C3.astype(np.int64) + 1).sum()) * 8
-    assert k6.max() == -(-(-(-total // 2048)) // 64) * 64 and k6.max() > 4096
-    # a tiny launch never goes below 256-key chunks
-    a1 = A.plan_items(c, np.full(4, 700, np.int32), np.ones(4, np.int32), 701 // 16 + 1)
-    a1 = a1[a1[:, 1] != 3]
-    k1 = (a1[:, 8] - a1[:, 7]).astype(np.int64)
-    assert k1.max() == 256 and len(a1) == 4 * 8 * 3
