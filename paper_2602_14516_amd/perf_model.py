@@ -160,9 +160,48 @@ def load_cost_model(path: str = COST_MODEL_PATH) -> dict:
         return json.load(f)
 
 
+def render_markdown(model: dict) -> str:
+    """The measured points and fitted lines of a cost model as markdown tables (the text under profiles/ is this)."""
+    sh = model["layer_shapes"]
+    pre = AlphaBetaFamily(np.array(model["tpre_l_incr"]), np.array(model["tpre_alpha"]), np.array(model["tpre_beta"]))
+    dec = AlphaBetaFamily(np.array(model["tdec_b"]), np.array(model["tdec_alpha"]), np.array(model["tdec_beta"]))
+    o = ["## Measured points", "", "| l_hist | l_incr | step us | algorithmic TFLOP/s | fitted line us |", "|---|---|---|---|---|"]
+    for h, l, t in model["points"]["T_pre"]:
+        fl = float(prefill_flops(h, l, sh["T_pre"]["Hq"], sh["T_pre"]["d"]))
+        o.append(f"| {int(h)} | {int(l)} | {t * 1e6:.1f} | {fl / t / 1e12:.0f} | {float(pre(l, h)[0]) * 1e6:.1f} |")
+    o += ["", "| b | sum C | step us | K/V GB/s | fitted line us |", "|---|---|---|---|---|"]
+    for b, c, t in model["points"]["T_dec"]:
+        by = float(decode_bytes(c, b, sh["T_dec"]["Hq"], sh["T_dec"]["Hkv"], sh["T_dec"]["d"]))
+        o.append(f"| {int(b)} | {int(c)} | {t * 1e6:.1f} | {by / t / 1e9:.0f} | {float(dec(b, c)[0]) * 1e6:.1f} |")
+    o += ["", "| l_ctx | pack us | unpack us | read + write GB/s (pack) |", "|---|---|---|---|"]
+    per_token = 2 * sh["T_kv"]["Hkv"] * sh["T_kv"]["d"] * 2
+    for l, tp, tu in model["points"]["T_kv"]:
+        o.append(f"| {int(l)} | {tp * 1e6:.1f} | {tu * 1e6:.1f} | {2 * per_token * l / tp / 1e9:.0f} |")
+    o += ["", "## Fitted lines (relative least squares)", "",
+          "T_pre(l_hist; l_incr) = alpha + beta x l_hist, one line per incremental length, interpolated in log(l_incr) between lines:", "",
+          "| l_incr | alpha us | beta ns per history token |", "|---|---|---|"]
+    for l, a, b in zip(model["tpre_l_incr"], model["tpre_alpha"], model["tpre_beta"]):
+        o.append(f"| {int(l)} | {a * 1e6:.1f} | {b * 1e9:.2f} |")
+    o += ["", f"residual on the grid: mean {model['tpre_rel_err'][0] * 100:.1f} %, max {model['tpre_rel_err'][1] * 100:.0f} %", "",
+          "T_dec(sum C; b) = alpha + beta x sum C, one line per batch size:", "", "| b | alpha us | beta ns per context token |", "|---|---|---|"]
+    for bb, a, b in zip(model["tdec_b"], model["tdec_alpha"], model["tdec_beta"]):
+        o.append(f"| {int(bb)} | {a * 1e6:.1f} | {b * 1e9:.3f} |")
+    kp, ku, kl = model["kv_pack"], model["kv_unpack"], model["kv_link"]
+    o += ["", f"residual on the grid: mean {model['tdec_rel_err'][0] * 100:.1f} %, max {model['tdec_rel_err'][1] * 100:.1f} %", "",
+          f"T_kv(l) per layer = pack + wire + unpack: pack {kp[0] * 1e6:.1f} us + {kp[1] * 1e9:.2f} ns/token, unpack {ku[0] * 1e6:.1f} us + "
+          f"{ku[1] * 1e9:.2f} ns/token (measured), wire {kl[0] * 1e6:.0f} us + {kl[1] * 1e9:.1f} ns/token (one xGMI link at its nominal "
+          f"{LINK_BYTES_PER_S / 1e9:.0f} GB/s, {per_token} bytes of K and V per token: not measurable on one GPU); "
+          f"kv_alpha = {model['kv_alpha'] * 1e6:.1f} us, kv_beta = {model['kv_beta'] * 1e9:.1f} ns/token."]
+    return "\n".join(o) + "\n"
+
+
 def _main(argv):
+    if len(argv) == 2 and argv[1] == "--render":
+        print(render_markdown(load_cost_model()), end="")
+        return 0
     if len(argv) != 2:
-        print("usage: python -m paper_2602_14516_amd.perf_model <output of `bench.py --only model`>")
+        print("usage: python -m paper_2602_14516_amd.perf_model <output of `bench.py --only model`>   (writes the cost model)\n"
+              "       python -m paper_2602_14516_amd.perf_model --render                             (prints it as markdown tables)")
         return 2
     lines = [l for l in open(argv[1]).read().splitlines() if l.startswith("{")]
     model = cost_model_from_sweep(json.loads(lines[-1]))

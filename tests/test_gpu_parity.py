@@ -239,7 +239,13 @@ def test_config3_full_size_mixed_batch():
     print("case: config 3 full size (mixed, one fused launch)", flush=True)
     b, db, out = _full_config(3, fn=A.mixed_batch_attn, per_req=4)
     info = A.plan_describe(db.cache, b.ctx_len, b.incr_len, b.block_table.shape[1])
-    assert info["num_wide_items"] > 0 and info["num_narrow_items"] > 0 and info["num_combine_items"] > 0
+    # 768 decode blocks on 256 workgroup slots: the planner cuts none of them, and the prefill rows are not cut either
+    assert info["num_wide_items"] > 0 and info["num_narrow_items"] == 96 * 8 and info["num_combine_items"] == 0
+    # the same launch with every key range cut in three (split-KV items of both kinds and the combine pass, full size)
+    print("case: config 3 full size, forced splits", flush=True)
+    out3 = run_attn(db, fn=A.mixed_batch_attn, force_kv_splits=3)       # (the append is idempotent)
+    compare(b, out3, rows=sample_rows(b, 4, seed=33), label="cfg3 forced splits")
+    assert np.abs(W.bf16_bits_to_f64(out) - W.bf16_bits_to_f64(out3)).max() <= 2e-2
 
 
 @pytest.mark.timeout(900)
