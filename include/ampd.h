@@ -179,8 +179,9 @@ ampd_status ampd_mixed_batch_attn(const ampd_kv_cache *cache, const ampd_batch *
                                   void *out, void *workspace, size_t workspace_bytes,
                                   void *stream);
 
-/* For callers that cannot allocate device memory (code under HIP graph capture, tight
- * serving loops, harnesses that forbid allocation): ampd_mixed_batch_attn with the work list
+/* For callers that cannot allocate device memory (code that runs while a HIP graph is being
+ * captured in the process, when hipMalloc is refused; tight serving loops; harnesses that
+ * forbid allocation): ampd_mixed_batch_attn with the work list
  * and the split-KV partial results in a static device array of AMPD_STATIC_WORKSPACE_BYTES
  * that the library's code object carries (one copy per GPU, held until the process ends)
  * instead of a caller workspace.  The call allocates nothing, on the device or pinned:
@@ -191,7 +192,9 @@ ampd_status ampd_mixed_batch_attn(const ampd_kv_cache *cache, const ampd_batch *
  * anything is enqueued.  Results are bitwise those of ampd_mixed_batch_attn.  All calls on one
  * GPU share the array: calls on the same stream are ordered and safe, calls that overlap on
  * different streams of one GPU race.  Nothing in the array has to start at zero (every
- * partial result is written before it is read), so it is never cleared. */
+ * partial result is written before it is read), so it is never cleared.  Like every
+ * attention call it stages its work list on the host when it is made: recording the call
+ * itself into a graph and replaying it is not supported. */
 #define AMPD_STATIC_WORKSPACE_BYTES (32u << 20)
 ampd_status ampd_mixed_batch_attn_static(const ampd_kv_cache *cache, const ampd_batch *batch,
                                          const void *q, const void *k_new, const void *v_new,
