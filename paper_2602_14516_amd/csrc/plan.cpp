@@ -11,7 +11,12 @@ namespace {
 constexpr int KV_TILE = 64;          // keys per LDS tile of a wide item; split points are multiples of it
 constexpr int MIN_NARROW_CHUNK = 256;
 constexpr int NARROW_ITEM_KEYS = 512;  // fixed cost of a narrow item (item, Q, page ids, first block, merge), in keys streamed
-constexpr int MIN_WIDE_CHUNK = 1024;
+constexpr int MIN_WIDE_CHUNK = 512;          // tiles of a launch without decode rows
+constexpr int MIN_WIDE_CHUNK_MIXED = 1024;   // ... of a mixed launch
+constexpr int WIDE_STAGE_KEYS = 128;   // a tile works through its keys in stages of 128: part of a stage costs a whole one
+constexpr int WIDE_ITEM_KEYS = 128;    // fixed cost of a tile (item, Q, first stage, output), in keys of a tile
+constexpr int WIDE_SPLIT_KEYS = 1408;  // a piece of a cut tile also writes a partial result of up to 256 rows that the
+                                       // combine pass reads again (fitted to single-request latencies, like the others)
 constexpr int NUM_XCD = 8;            // accelerator dies; workgroup i is dispatched to die i % NUM_XCD
 
 inline int64_t round_up(int64_t x, int64_t m) { return (x + m - 1) / m * m; }
@@ -40,7 +45,15 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
     std::vector<QBlock> qb;
     int64_t narrow_keys = 0;
     int64_t n_wide = 0;
-    std::vector<std::pair<int32_t, int32_t>> narrow_runs;   // (keys, number of consecutive narrow blocks with that many)
+    // (keys, number of blocks with that many): what the split policy needs to know of the blocks; noted for KV head 0
+    // and multiplied by the number of KV heads afterwards
+    std::vector<std::pair<int32_t, int32_t>> narrow_runs, wide_runs;
+    auto note = [](std::vector<std::pair<int32_t, int32_t>>& runs, int32_t keys) {
+        if (!runs.empty() && runs.back().first == keys)
+            ++runs.back().second;
+        else
+            runs.emplace_back(keys, 1);
+    };
     for (int r = 0; r < num_reqs; ++r) {
         const int C = ctx_len[r], L = incr_len[r];
         if (L <= 0) continue;
@@ -52,10 +65,7 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                 if ((int64_t)L * gn <= 32) {
                     qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_NARROW), 0, L, C + L, L * gn, KIND_NARROW});
                     narrow_keys += C + L;
-                    if (!narrow_runs.empty() && narrow_runs.back().first == C + L)
-                        ++narrow_runs.back().second;
-                    else
-                        narrow_runs.emplace_back(C + L, 1);
+                    if (kvh == 0) note(narrow_runs, C + L);
                 } else {
                     // A tile that is not full costs its workgroup nearly as much per key as a full one, so the
                     // remainder of the row goes into the FIRST tile, which sees the fewest keys.
@@ -65,68 +75,98 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
                         const int nq = q0 ? tq : first;
                         qb.push_back(QBlock{r, pack_heads(kvh, g0, gn, KIND_WIDE), q0, nq, C + q0 + nq, nq * gn, KIND_WIDE});
                         ++n_wide;
+                        if (kvh == 0) note(wide_runs, C + q0 + nq);
                     }
                 }
             }
         }
     }
 
+    for (auto& r : narrow_runs) r.second *= s.Hkv;
+    for (auto& r : wide_runs) r.second *= s.Hkv;
+
     // 2. split policy (chunk sizes in keys, multiples of KV_TILE)
+    // An item costs a few microseconds around its key range (item, Q, page ids and first block before the first key;
+    // merge of the waves or the store of a partial result after the last), and a CU runs one item at a time, so
+    // nothing hides that: few, long items win as long as the slots (resident workgroups) stay evenly loaded.
+    // Candidates are the smallest chunks whose items fit ONE round on all, half or a quarter of the slots, the chunks
+    // that give ~2, 3, 4 items per slot, and (tiles) no cut at all.  One round lasts as long as its longest piece; several rounds about a slot's
+    // share of the keys plus half a longest piece; every item adds its fixed cost (item_keys, in keys streamed), and
+    // every piece of a cut block the cost of its partial result (split_keys: written, and read again by the combine pass).
     int64_t narrow_chunk = 1 << 30, wide_chunk = 1 << 30;
-    if (opt.force_kv_splits <= 0) {
-        if (narrow_keys > 0) {
-            // An item costs a few microseconds before its first key arrives and after its last (item, Q, page ids,
-            // first block; merge of the waves), and a CU runs one item at a time, so nothing hides that: few, long items
-            // win as long as the slots (resident workgroups) stay evenly loaded.
-            //  - Two or more rows per slot: whole rows balance well by themselves (longest first); only a row longer
-            //    than a slot's share of the keys is cut.
-            //  - Fewer: candidates are the smallest chunk whose items fit one round on the slots (p = 1) and the
-            //    chunks that give ~p items per slot, p = 2, 3, 4.  One round lasts as long as its longest piece; several
-            //    rounds about a slot's share of the keys plus half a longest piece; every item adds its fixed cost.
-            const int64_t slots = opt.wg_slots;
-            auto count_items = [&](int64_t chunk) {
-                int64_t n = 0;
-                for (const auto& r : narrow_runs) n += ceil_div(r.first, chunk) * r.second;
-                return n;
-            };
-            int64_t n_blocks = 0, max_len = 0;
-            for (const auto& r : narrow_runs) {
-                n_blocks += r.second;
-                max_len = std::max<int64_t>(max_len, r.first);
+    auto choose_chunk = [&](const std::vector<std::pair<int32_t, int32_t>>& runs, int64_t slots, int64_t granule,
+                            int64_t min_chunk, int64_t item_keys, int64_t split_keys) {
+        auto count_items = [&](int64_t chunk, int64_t* pieces_of_cut_blocks = nullptr) {
+            int64_t n = 0, cut = 0;
+            for (const auto& r : runs) {
+                const int64_t pieces = ceil_div(r.first, chunk);
+                n += pieces * r.second;
+                if (pieces > 1) cut += pieces * r.second;
             }
-            const int64_t base = ceil_div(narrow_keys, slots);
-            if (n_blocks >= 2 * slots) {
-                narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(base, KV_TILE));
-            } else {
-                int64_t best_cost = -1;
-                for (int per_slot = 1; per_slot <= 4; ++per_slot) {
-                    int64_t chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(ceil_div(base, per_slot), KV_TILE));
-                    if (per_slot == 1 && n_blocks <= slots && count_items(chunk) > slots) {
-                        int64_t lo = chunk / KV_TILE, hi = ceil_div(max_len, KV_TILE);      // count(hi) = n_blocks <= slots
-                        while (lo + 1 < hi) {
-                            const int64_t mid = (lo + hi) / 2;
-                            (count_items(mid * KV_TILE) > slots ? lo : hi) = mid;
-                        }
-                        chunk = hi * KV_TILE;
-                    }
-                    const int64_t n = count_items(chunk);
-                    const int64_t piece = std::min(chunk, max_len);
-                    const int64_t cost = n <= slots ? piece + NARROW_ITEM_KEYS
-                                                    : base + piece / 2 + ceil_div(NARROW_ITEM_KEYS * n, slots);
-                    if (best_cost < 0 || cost < best_cost) {
-                        best_cost = cost;
-                        narrow_chunk = chunk;
-                    }
-                    if (chunk == MIN_NARROW_CHUNK) break;          // (smaller chunks are not allowed)
-                }
-            }
+            if (pieces_of_cut_blocks) *pieces_of_cut_blocks = cut;
+            return n;
+        };
+        int64_t n_blocks = 0, max_len = 0, keys = 0;
+        for (const auto& r : runs) {
+            n_blocks += r.second;
+            max_len = std::max<int64_t>(max_len, r.first);
+            keys += (int64_t)r.first * r.second;
         }
-        if (n_wide > 0 && n_wide < 2 * (int64_t)opt.wg_slots) {
-            int64_t max_keys = 0;
-            for (const QBlock& b : qb)
-                if (b.kind == KIND_WIDE) max_keys = std::max<int64_t>(max_keys, b.nkeys);
-            const int64_t want = ceil_div(2 * (int64_t)opt.wg_slots, n_wide);
-            wide_chunk = std::max<int64_t>(MIN_WIDE_CHUNK, round_up(ceil_div(max_keys, want), KV_TILE));
+        const int64_t base = ceil_div(keys, slots);
+        int64_t best_cost = -1, best = 1 << 30;
+        auto consider = [&](int64_t chunk) {
+            int64_t cut = 0;
+            const int64_t n = count_items(chunk, &cut);
+            const int64_t piece = std::min(chunk, max_len);
+            const int64_t cost = (n <= slots ? piece + item_keys : base + piece / 2 + ceil_div(item_keys * n, slots)) +
+                                 ceil_div(split_keys * cut, slots);
+            if (best_cost < 0 || cost < best_cost) {
+                best_cost = cost;
+                best = chunk;
+            }
+        };
+        // one round on all, half or a quarter of the slots: the smallest chunk whose items fit
+        for (int64_t target = slots; target >= slots / 4 && target >= n_blocks; target /= 2) {
+            int64_t lo = min_chunk / granule - 1, hi = std::max<int64_t>(min_chunk / granule, ceil_div(max_len, granule));
+            while (lo + 1 < hi) {                          // count(hi) = n_blocks <= target
+                const int64_t mid = (lo + hi) / 2;
+                (count_items(mid * granule) > target ? lo : hi) = mid;
+            }
+            consider(hi * granule);
+        }
+        // ~2, 3, 4 items per slot
+        for (int per_slot = n_blocks <= slots ? 2 : 1; per_slot <= 4; ++per_slot) {
+            const int64_t chunk = std::max<int64_t>(min_chunk, round_up(ceil_div(base, per_slot), granule));
+            consider(chunk);
+            if (chunk == min_chunk) break;                 // (smaller chunks are not allowed)
+        }
+        if (split_keys > 0) consider(round_up(max_len, granule));    // whole blocks
+        return best;
+    };
+    if (opt.force_kv_splits <= 0) {
+        const int64_t slots = opt.wg_slots;
+        if (narrow_keys > 0) {
+            // Two or more rows per slot: whole rows balance well by themselves (longest first); only a row longer
+            // than a slot's share of the keys is cut.
+            int64_t n_blocks = 0;
+            for (const auto& r : narrow_runs) n_blocks += r.second;
+            if (n_blocks >= 2 * slots)
+                narrow_chunk = std::max<int64_t>(MIN_NARROW_CHUNK, round_up(ceil_div(narrow_keys, slots), KV_TILE));
+            else
+                narrow_chunk = choose_chunk(narrow_runs, slots, KV_TILE, MIN_NARROW_CHUNK, NARROW_ITEM_KEYS, 0);
+        }
+        // tiles: cut only when fewer than two per slot exist
+        if (n_wide > 0 && n_wide < 2 * slots) {
+            if (narrow_keys == 0) {
+                wide_chunk = choose_chunk(wide_runs, slots, WIDE_STAGE_KEYS, MIN_WIDE_CHUNK, WIDE_ITEM_KEYS, WIDE_SPLIT_KEYS);
+            } else {
+                // next to decode rows (a mixed batch) the tiles are not alone on the slots and the estimate above does
+                // not hold; measured best there: about two pieces per slot, cut by the longest tile, at least 1024 keys
+                int64_t max_keys = 0;
+                for (const auto& r : wide_runs) max_keys = std::max<int64_t>(max_keys, r.first);
+                const int64_t want = ceil_div(2 * slots, n_wide);
+                wide_chunk = std::max<int64_t>(MIN_WIDE_CHUNK_MIXED, round_up(ceil_div(max_keys, want), KV_TILE));
+            }
         }
     }
 

@@ -190,6 +190,34 @@ def test_planner_narrow_chunks_follow_the_number_of_workgroup_slots():
     assert k1.max() == 256 and len(a1) == 4 * 8 * 3
 
 
+def test_planner_cuts_the_tiles_of_a_small_prefill_for_one_round():
+    """A single incremental prefill (the paper's T_pre(l_hist, l_incr) case) has fewer tiles than workgroup slots: the key
+    ranges of its tiles are cut so that the pieces fit one round on the 256 slots (all, half or a quarter of them), in
+    whole 128-key stages, and not at all when the tiles already fill the slots or a cut would cost more than it saves."""
+    c = shape_cache(32, 8, 128, 16)
+    def plan(h, l):
+        C, L = np.array([h], np.int32), np.array([l], np.int32)
+        info = A.plan_describe(c, C, L, (h + l) // 16 + 1)
+        a = A.plan_items(c, C, L, (h + l) // 16 + 1)
+        a = a[a[:, 1] == 0]
+        return info, (a[:, 8] - a[:, 7]).astype(np.int64), a
+    info, keys, a = plan(4096, 512)                      # 64 tiles of 4 160 .. 4 608 keys -> 4 pieces each
+    assert info["num_wide_items"] == 256 and info["num_combine_items"] == 64 and keys.max() == 1152
+    info, keys, a = plan(16384, 64)                      # 8 tiles of 16 448 keys -> 16 pieces each on half the slots
+    assert info["num_combine_items"] == 8 and info["num_wide_items"] <= 256 and keys.max() % 128 == 0
+    info, keys, a = plan(1024, 2048)                     # 256 tiles: one round as they are
+    assert info["num_wide_items"] == 256 and info["num_combine_items"] == 0
+    info, keys, a = plan(0, 512)                         # short rows: nothing worth cutting
+    assert info["num_combine_items"] == 0
+    for h, l in ((4096, 512), (16384, 64), (1024, 512)): # pieces of a tile are contiguous and cover [0, C + q0 + nq)
+        info, keys, a = plan(h, l)
+        for kvh in (0, 7):
+            for q0 in np.unique(a[:, 5]):
+                m = a[(a[:, 2] == kvh) & (a[:, 5] == q0)]
+                m = m[np.argsort(m[:, 7])]
+                assert m[0, 7] == 0 and np.all(m[1:, 7] == m[:-1, 8]) and m[-1, 8] == h + q0 + m[0, 6]
+
+
 def check_xcd_queues(a, min_balance):
     """Workgroup i runs on die i % 8: the tiles of one K/V stream (request, KV head) share a die, next to each
     other and longest first, and the dies carry equal wide work."""
