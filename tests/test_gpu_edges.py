@@ -40,7 +40,7 @@ def test_head_group_shapes(name, C, L, Hq, Hkv, d, P):
 
 
 @pytest.mark.parametrize("C,L,Hq,Hkv", [
-    ([1211], [338], 16, 2),                          # 2 K/V streams for 8 dies: pieces, levelling, null items
+    ([897], [287], 16, 2),                           # 2 K/V streams for 8 dies: pieces, levelling, null items
     ([1355, 407, 542], [618, 147, 63], 8, 1),        # 3 streams of very different weight
     ([1325, 1308, 459, 27], [549, 501, 544, 20], 8, 1),
 ])

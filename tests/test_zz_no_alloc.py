@@ -47,7 +47,7 @@ def test_static_workspace_entry_point_matches_the_workspace_one_on_two_calls_in_
 
 @pytest.mark.parametrize("name,n,c,l,Hq,Hkv", [
     ("work list beyond one staging buffer", 1500, 40000, 1, 64, 8),       # 12 000 work items = 600 KB of work list
-    ("partial results beyond the static array", 1, 600000, 32, 8, 1),     # one 256-row tile cut into 512 key pieces = 68 MB
+    ("partial results beyond the static array", 300, 20000, 32, 8, 1),    # 300 256-row tiles cut into 3 key pieces each = 114 MiB
 ])
 def test_static_workspace_entry_point_rejects_what_does_not_fit(name, n, c, l, Hq, Hkv):
     """Both limits are checked on the host before anything is enqueued.  (The inputs are harmless even if they were
