@@ -71,6 +71,7 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
     off = np.concatenate([[0], np.cumsum(L)])
     copied = np.zeros(int(off[-1]), np.int32)          # packed rows moved to their pages by append items
     seen_append = False
+    slots = []                                         # partial-result slots [begin, end) in floats
     for req, kind, kvh, g0, gn, q0, nq, kb, ke, po in items.tolist():
         if kind == 2:                                  # null item: pads a die's queue, does no work
             assert req == -1 and nq == 0 and po == -1
@@ -83,6 +84,8 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
         assert not seen_append, "append items close the work list"
         assert 0 < gn <= 32 and g0 + gn <= G and nq > 0 and kb < ke and kb % 64 == 0
         assert nq * gn <= (256 if kind == 0 else 32)
+        if po >= 0:
+            slots.append((po, po + nq * gn * (d + 2)))
         for g in range(g0, g0 + gn):
             for i in range(q0, q0 + nq):
                 ranges.setdefault((req, kvh * G + g, i), []).append((kb, ke))
@@ -97,6 +100,9 @@ def coverage_check(Hq, Hkv, d, P, C, L, splits=0):
                     pos = ke
                 assert pos >= vis and rs[-1][0] < vis or len(rs) == 1 or rs[-1][0] < C[r] + L[r]
                 assert pos >= vis
+    slots.sort()
+    for (b0, e0), (b1, e1) in zip(slots, slots[1:]):
+        assert e0 <= b1, "partial-result slots overlap"
     assert not ranges, "items refer to queries that do not exist"
     assert np.all(copied == 1), "every new token is written to its page exactly once"
     return items
@@ -111,6 +117,19 @@ def test_planner_covers_every_causal_pair_exactly_once(splits):
         L[0] = 1
         C[1] = 0
         coverage_check(Hq, Hkv, d, P, C, L, splits)
+
+
+@pytest.mark.parametrize("geom,C,L", [
+    ((32, 8, 128, 16), [4096], [512]),                 # a lone prefill whose tiles are cut for one round
+    ((32, 8, 128, 16), [16384], [64]),
+    ((32, 8, 128, 16), [1024], [2048]),                # tiles that fill the slots uncut
+    ((8, 1, 128, 32), [57000, 60000, 50000, 61000], [1, 1, 1, 1]),     # long decode rows, one round of key ranges
+    ((32, 8, 128, 16), [6000] * 26 + [3000], [1] * 26 + [300]),        # decode rows next to a prefill row
+    ((32, 8, 128, 16), [9000] * 40, [1] * 40),         # 320 decode blocks on 256 slots
+])
+def test_planner_coverage_where_the_split_policy_cuts(geom, C, L):
+    Hq, Hkv, d, P = geom
+    coverage_check(Hq, Hkv, d, P, C, L)
 
 
 def test_planner_coverage_on_drawn_shapes():
