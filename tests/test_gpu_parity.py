@@ -110,6 +110,18 @@ def test_many_kv_splits_odd_row_counts(d, G):
     compare(b, out, label=f"splits40 d{d} G{G}")
 
 
+@pytest.mark.parametrize("C,L", [(4096, 512), (16384, 64), (1024, 2048), (700, 1024)])
+def test_lone_prefill_whose_tiles_the_planner_cuts_for_one_round(C, L):
+    """A single request with fewer query tiles than CUs: the planner cuts the key ranges of its tiles (4 and 16 pieces
+    in the first two cases, none in the third, two for the longer tiles of the fourth); sampled rows against the oracle."""
+    print(f"case: lone prefill C={C} L={L}", flush=True)
+    b = W.make_batch([C], [L], 32, 8, 128, 16, seed=C + L, poison=True)
+    db = DevBatch(b)
+    out = run_attn(db)
+    check_append(db)
+    compare(b, out, rows=sample_rows(b, 24, seed=5), label=f"lone prefill {C}+{L}")
+
+
 def test_mixed_equals_separate_sub_batches():
     print("case: mixed vs separate", flush=True)
     C = [700, 90, 2048, 5, 300, 1500]
