@@ -611,6 +611,16 @@ def main():
                              "rows": int(big.sum()), "kernel_ms": float(ktb[0])}
     # the same step in the steady state of a long run, for comparison with `value` at the requested steps / warm-up
     steady_ms = time_calls(torch, step, 300, 20)
+    # the same batch over an 8-bit cache (quantising append launch, then the attention launch that widens the codes on their
+    # way into LDS): timing only, device-drawn codes; parity of this path is covered by tests/test_gpu_fp8.py
+    db8 = device_batch(torch, A, W, batch.ctx_len, batch.incr_len, dict(Hq=batch.Hq, Hkv=batch.Hkv, d=batch.d, P=batch.P), seed=8, fp8=True)
+    step8 = make_runner(torch, A, db8, "prefill")
+    ms8 = time_calls(torch, step8, 50, 10)
+    kt8 = kernel_times(torch, A, step8, 10)
+    kv8 = {"ms_per_step": ms8, "attn_kernel_ms": float(kt8[0]), "append_ms": float(kt8[2]),
+           "frac_of_bf16_peak_step": flops / (ms8 * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
+           "frac_of_bf16_peak_attn_kernel": flops / (kt8[0] * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}
+    del db8, step8
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -626,7 +636,8 @@ def main():
                    "sum_L": int(batch.incr_len.sum()), "sum_T": int((batch.ctx_len + batch.incr_len).sum()),
                    "algorithmic_TFLOP": flops / 1e12, "frac_of_bf16_peak": flops / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS,
                    "steady_state_300_steps": {"ms_per_step": steady_ms, "TFLOPs": flops / (steady_ms * 1e-3) / 1e12,
-                                              "frac_of_bf16_peak": flops / (steady_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS}},
+                                              "frac_of_bf16_peak": flops / (steady_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS},
+                   "same_batch_over_8bit_cache": kv8},
         "roofline": roof, "cpu_baseline": cpu, "cfg4": cfg4, "mixed": mixed, "trace": trace,
     }
     print(json.dumps(line))
