@@ -233,7 +233,19 @@ def data_dependence(torch, A, W, steps=100, warmup=20):
     run("V = 0", zero=V)
     run("all 0.5", fill=0.5)
     run("Q, K, V ~ N(0,1) again")
-    return {"only": "datadep", "workload": "configuration 2, one step", "runs": out}
+    del db, step, saved
+    torch.cuda.empty_cache()
+    # context, not part of the path: a plain bf16 GEMM of the vendor library (torch.matmul) on the same device shows the
+    # same dependence, i.e. what the chip sustains on operands of these values
+    gemm = []
+    n = 8192
+    a = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    b = torch.randn(n, n, device="cuda", dtype=torch.bfloat16)
+    for tag, (x, y) in (("N(0,1)", (a, b)), ("all zero", (torch.zeros_like(a), torch.zeros_like(b))), ("N(0,1) again", (a, b))):
+        ms = time_calls(torch, lambda: torch.matmul(x, y), 50, 10)
+        gemm.append({"operands": tag, "ms": ms, "frac_of_bf16_peak": 2 * n ** 3 / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS})
+    return {"only": "datadep", "workload": "configuration 2, one step", "runs": out,
+            "library_gemm_8192_cubed_bf16": gemm}
 
 
 def model_sweep(torch, A, W):
