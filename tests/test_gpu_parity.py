@@ -122,6 +122,41 @@ def test_lone_prefill_whose_tiles_the_planner_cuts_for_one_round(C, L):
     compare(b, out, rows=sample_rows(b, 24, seed=5), label=f"lone prefill {C}+{L}")
 
 
+def test_seeded_batches_in_the_regimes_of_the_split_policy():
+    """Thirty-six seeded random batches, six in each regime in which the planner cuts key ranges differently: a lone
+    prefill (tiles cut for one round), a few long decode rows (one round of key ranges), a decode batch with one to three
+    blocks per workgroup slot, decode rows next to a prefill row, a small ragged batch, several prefill rows; head
+    geometry (odd group sizes included), head dim and page size drawn as well, some with forced splits."""
+    rng = np.random.default_rng(20260215)
+    for case in range(36):
+        regime = case % 6
+        Hkv = int(rng.choice([1, 2, 8])); G = int(rng.choice([1, 3, 4, 5, 8, 16])); d = int(rng.choice([64, 128])); P = int(rng.choice([16, 32]))
+        if regime == 0:
+            C = [int(rng.integers(0, 20000))]; L = [int(rng.integers(33, 1500))]
+        elif regime == 1:
+            n = int(rng.integers(1, 6)); C = [int(rng.integers(2000, 40000)) for _ in range(n)]; L = [1] * n
+        elif regime == 2:
+            n = int(rng.integers(20, 90)); C = [int(rng.integers(100, 6000)) for _ in range(n)]; L = [1] * n
+        elif regime == 3:
+            n = int(rng.integers(4, 30)); C = [int(rng.integers(100, 8000)) for _ in range(n)]; L = [1] * n
+            for _ in range(int(rng.integers(1, 3))):
+                C.append(int(rng.integers(0, 6000))); L.append(int(rng.integers(2, 900)))
+        elif regime == 4:
+            n = int(rng.integers(1, 8)); C = [int(rng.integers(0, 1200)) for _ in range(n)]; L = [int(rng.integers(0, 300)) for _ in range(n)]
+            if sum(L) == 0:
+                L[0] = 3
+        else:
+            n = int(rng.integers(2, 6)); C = [int(rng.integers(0, 5000)) for _ in range(n)]; L = [int(rng.integers(40, 700)) for _ in range(n)]
+        if Hkv * G * d * sum(c + l for c, l in zip(C, L)) > 6e8:          # bound the host-side pool
+            Hkv = 1
+        splits = int(rng.choice([0, 0, 0, 2, 7]))
+        print(f"case {case}: regime {regime} Hq={Hkv * G} Hkv={Hkv} d={d} P={P} n={len(C)} sum C={sum(C)} sum L={sum(L)} splits={splits}", flush=True)
+        db = DevBatch(W.make_batch(C, L, Hkv * G, Hkv, d, P, seed=10000 + case, poison=True))
+        out = run_attn(db, fn=A.mixed_batch_attn if case % 2 else A.incr_prefill_attn, force_kv_splits=splits)
+        check_append(db)
+        compare(db.b, out, rows=sample_rows(db.b, 6, seed=case) if sum(L) > 12 else None, label=f"regime {regime} case {case}")
+
+
 def test_mixed_equals_separate_sub_batches():
     print("case: mixed vs separate", flush=True)
     C = [700, 90, 2048, 5, 300, 1500]
