@@ -228,6 +228,7 @@ ampd_status stage_plan(DeviceState& d, const Plan& plan, void* workspace, bool m
     std::memcpy(h + plan.off_reqs, plan.reqs.data(), plan.reqs.size() * sizeof(ReqInfo));
     std::memcpy(h + plan.off_items, plan.items.data(), plan.items.size() * sizeof(Item));
     if (!plan.combs.empty()) std::memcpy(h + plan.off_combs, plan.combs.data(), plan.combs.size() * sizeof(CombItem));
+    std::memcpy(h + plan.off_queues, plan.queue_heads, sizeof(plan.queue_heads));
     up->src = h;
     up->dst = workspace;
     up->bytes = (size_t)plan.plan_bytes;
@@ -291,6 +292,8 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     p.items = reinterpret_cast<const Item*>(ws + plan.off_items);
     p.combs = reinterpret_cast<const CombItem*>(ws + plan.off_combs);
     p.partial = reinterpret_cast<float*>(ws + plan.off_partial);
+    p.queue_heads = reinterpret_cast<int32_t*>(ws + plan.off_queues);
+    p.nitems = (int32_t)plan.items.size();
     p.Hq = c->num_q_heads;
     p.Hkv = c->num_kv_heads;
     p.P = c->page_size;
@@ -302,7 +305,7 @@ ampd_status do_attn(const ampd_kv_cache* c, const ampd_batch* b, const Plan& pla
     const int kvt = c->kv_dtype == AMPD_KV_FP8_E4M3 ? KV_FP8 : KV_BF16;
 
     if (timing) HIP_TRY(hipEventRecord(t_ev[1], st));
-    HIP_TRY(launch_attn(p, c->head_dim, kvt, (int)plan.items.size(), st));
+    HIP_TRY(launch_attn(p, c->head_dim, kvt, plan.grid, st));
     if (timing) HIP_TRY(hipEventRecord(t_ev[2], st));
     int comb_rows = 0, comb_splits = 0;
     for (const CombItem& ci : plan.combs) {

@@ -29,6 +29,9 @@ struct AttnParams {
     // out of the slot precedes it in stream order): the first workgroup stores slot_seq to *slot_flag (pinned host memory).
     uint32_t* slot_flag;
     uint32_t slot_seq;
+    // Persistent launch (more items than workgroups): per-die queue heads in the workspace, see Plan::queue_heads.
+    int32_t* queue_heads;
+    int32_t nitems;
 };
 
 struct AppendParams {
@@ -51,7 +54,7 @@ struct AppendParams {
 
 // h_src: pinned, device-visible host memory; bytes is rounded up to 16
 hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream_t st);
-hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st);
+hipError_t launch_attn(const AttnParams& p, int D, int kvt, int grid, hipStream_t st);
 // max_rows: the largest nq * heads among the split tiles (sizes the second grid dimension)
 hipError_t launch_combine(const AttnParams& p, int D, int ncombs, int max_rows, int max_splits, hipStream_t st);
 hipError_t launch_append(const AppendParams& p, int kvt, int max_pages_touched, int nreq, hipStream_t st);

@@ -909,21 +909,77 @@ __device__ __forceinline__ void append_body(const AttnParams& p, const ItemCtx& 
 // ---------------------------------------------------------------------------------------------
 // the fused attention launch: one workgroup per work item, wide and narrow items in one grid
 
+// Next item of die queue q (items q, q + NUM_QUEUES, ...), or -1 when the queue is used up.
+__device__ __forceinline__ int take_item(const AttnParams& p, int q) {
+    const int pos = __hip_atomic_fetch_add(p.queue_heads + q, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int idx = q + NUM_QUEUES * pos;
+    return idx < p.nitems ? idx : -1;
+}
+// An item of the queue with the most items left, or -1 when every queue is used up (bounded: every failed
+// attempt means another workgroup took the item).
+__device__ __forceinline__ int steal_item(const AttnParams& p) {
+    for (int attempt = 0; attempt < 4 * NUM_QUEUES; ++attempt) {
+        int best = -1, best_left = 0;
+        for (int q = 0; q < NUM_QUEUES; ++q) {
+            const int pos = __hip_atomic_load(p.queue_heads + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            const int left = (p.nitems - q + NUM_QUEUES - 1) / NUM_QUEUES - pos;
+            if (left > best_left) {
+                best_left = left;
+                best = q;
+            }
+        }
+        if (best < 0) return -1;
+        const int idx = take_item(p, best);
+        if (idx >= 0) return idx;
+    }
+    return -1;
+}
+
 template <int D, int KVT>
-__global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
-    __shared__ __attribute__((aligned(16))) char smem_raw[Geo<D>::SMEM];
-    const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
-    if (blockIdx.x == 0 && threadIdx.x == 0 && p.slot_flag)   // releases the host's staging slot (see AttnParams)
-        __hip_atomic_store(p.slot_flag, p.slot_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    const int kind = (p.items[blockIdx.x].heads >> 24) & 0xff;
+__device__ __forceinline__ void run_item(const AttnParams& p, int idx, uint32_t smem) {
+    const int kind = (p.items[idx].heads >> 24) & 0xff;
     if (kind == KIND_NULL) return;                         // a filler that keeps the following items on their XCD
-    const ItemCtx ic = load_item(p, blockIdx.x);
+    const ItemCtx ic = load_item(p, idx);
     if (kind == KIND_WIDE)
         wide_body<D, KVT>(p, ic, smem);
     else if (kind == KIND_NARROW)
         narrow_body<D, KVT>(p, ic, smem);
     else if (KVT == KV_BF16)
         append_body(p, ic, D);
+}
+
+// One workgroup per work item when the items fit one round on the CUs (gridDim.x = number of items).  Otherwise
+// gridDim.x persistent workgroups: workgroup i runs item i, then items of the queue of its die (workgroup i of a launch
+// is dispatched to die i % NUM_QUEUES, and so were the items of queue i % NUM_QUEUES meant to be: their K/V streams share
+// that die's L2), and when that queue is used up it helps out on the queue with the most items left, so that the dies
+// finish together.
+// No workgroup ever waits for another: every loop ends when the queues are used up.
+template <int D, int KVT>
+__global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
+    __shared__ __attribute__((aligned(16))) char smem_raw[Geo<D>::SMEM];
+    __shared__ int s_next;
+    const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && p.slot_flag)   // releases the host's staging slot (see AttnParams)
+        __hip_atomic_store(p.slot_flag, p.slot_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    if (p.nitems <= (int)gridDim.x) {
+        run_item<D, KVT>(p, blockIdx.x, smem);
+        return;
+    }
+    const int home = blockIdx.x % NUM_QUEUES;
+    int idx = blockIdx.x;
+    for (;;) {
+        run_item<D, KVT>(p, idx, smem);
+        __syncthreads();                                   // every wave is done with this item's LDS (and has read s_next)
+        if (threadIdx.x == 0) {
+            // taken when the item is done, not before: the queues are ordered longest first, and an item reserved
+            // early would go to a workgroup by its position in the launch instead of to the one that is free first
+            const int next = take_item(p, home);
+            s_next = next >= 0 ? next : steal_item(p);
+        }
+        __syncthreads();
+        idx = s_next;
+        if (idx < 0) return;
+    }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -1213,17 +1269,17 @@ hipError_t launch_upload(const void* h_src, void* d_dst, size_t bytes, hipStream
 }
 
 template <int D, int KVT>
-static hipError_t launch_attn_t(const AttnParams& p, int nitems, hipStream_t st) {
-    hipLaunchKernelGGL((attn_kernel<D, KVT>), dim3(nitems), dim3(AWG), 0, st, p);
+static hipError_t launch_attn_t(const AttnParams& p, int grid, hipStream_t st) {
+    hipLaunchKernelGGL((attn_kernel<D, KVT>), dim3(grid), dim3(AWG), 0, st, p);
     return hipGetLastError();
 }
 
-hipError_t launch_attn(const AttnParams& p, int D, int kvt, int nitems, hipStream_t st) {
-    if (nitems <= 0) return hipSuccess;
-    if (D == 128 && kvt == KV_BF16) return launch_attn_t<128, KV_BF16>(p, nitems, st);
-    if (D == 64 && kvt == KV_BF16) return launch_attn_t<64, KV_BF16>(p, nitems, st);
-    if (D == 128 && kvt == KV_FP8) return launch_attn_t<128, KV_FP8>(p, nitems, st);
-    if (D == 64 && kvt == KV_FP8) return launch_attn_t<64, KV_FP8>(p, nitems, st);
+hipError_t launch_attn(const AttnParams& p, int D, int kvt, int grid, hipStream_t st) {
+    if (grid <= 0) return hipSuccess;
+    if (D == 128 && kvt == KV_BF16) return launch_attn_t<128, KV_BF16>(p, grid, st);
+    if (D == 64 && kvt == KV_BF16) return launch_attn_t<64, KV_BF16>(p, grid, st);
+    if (D == 128 && kvt == KV_FP8) return launch_attn_t<128, KV_FP8>(p, grid, st);
+    if (D == 64 && kvt == KV_FP8) return launch_attn_t<64, KV_FP8>(p, grid, st);
     return hipErrorInvalidValue;
 }
 

@@ -25,6 +25,7 @@ namespace ampd {
 enum : int32_t { KIND_WIDE = 0, KIND_NARROW = 1, KIND_NULL = 2, KIND_APPEND = 3 };
 
 constexpr int ATTN_WAVES = 8;      // waves of an attention workgroup (one workgroup per CU)
+constexpr int NUM_QUEUES = 8;      // accelerator dies (XCDs): workgroup i of a launch is dispatched to die i % 8
 constexpr int APPEND_MAX_REQS = 128;   // requests per append launch (their lengths travel as kernel arguments)
 
 struct ReqInfo {          // 16 B, one per request, device-visible
@@ -77,8 +78,14 @@ struct Plan {
     int64_t num_wide = 0, num_narrow = 0, num_append = 0;
     int64_t partial_floats = 0;
     int64_t sum_L = 0;
-    // byte layout of the device copy: [reqs][items][combs], each 256 B aligned
-    int64_t off_reqs = 0, off_items = 0, off_combs = 0, plan_bytes = 0;
+    // A launch with tiles in it and more items than workgroup slots runs `grid` persistent workgroups (otherwise grid = the
+    // number of items, one workgroup each): workgroup i starts with item i
+    // and then takes items from the queue of its die (queue q = items q, q + NUM_QUEUES, ...; queue_heads[q] = the
+    // queue's position of the first item nobody has started), helping out on other queues when its own is empty.
+    int32_t grid = 0;
+    int32_t queue_heads[NUM_QUEUES] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // byte layout of the device copy: [reqs][items][combs][queue heads], each 256 B aligned
+    int64_t off_reqs = 0, off_items = 0, off_combs = 0, off_queues = 0, plan_bytes = 0;
     int64_t off_partial = 0, total_bytes = 0;
 };
 
