@@ -646,10 +646,10 @@ __device__ __forceinline__ void store_result(const AttnParams& p, const ItemCtx&
 // 8-bit cache: register-staged and widened on the way into LDS, by all waves.
 
 template <int D, int KVT>
-__device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
+__device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem, int tid) {
     using G_ = Geo<D>;
     constexpr bool DMA = KVT == KV_BF16;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int tqw = 32 / ic.gn;                            // tokens per wave
     const int row = lane & 31;
     const int tl = row / ic.gn, hg = row - tl * ic.gn;
@@ -754,9 +754,9 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
 // own LDS region, and merge their (m, l, O) through LDS at the end
 
 template <int D, int KVT>
-__device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem) {
+__device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem, int tid) {
     using G_ = Geo<D>;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = tid >> 6;
     const int row = lane & 31;
     const int tl = row / ic.gn, hg = row - tl * ic.gn;
     const bool valid = tl < ic.nq;
@@ -884,14 +884,14 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
 // the same launch never read these page slots (they take new tokens from the packed rows), so the two kinds
 // need no order among themselves.
 
-__device__ __forceinline__ void append_body(const AttnParams& p, const ItemCtx& ic, int D) {
+__device__ __forceinline__ void append_body(const AttnParams& p, const ItemCtx& ic, int D, int tid) {
     const int cpt = p.Hkv * D / 8;                           // 16-byte chunks per packed row (one of K or V)
     const int cph = D / 8;
     const int first_row = ic.row_off + ic.q0;                // packed row of the item's first token
     const int total = ic.nq * cpt;
     int r = ic.req;                                          // request of the row this thread is at: rows only move forward
     ReqInfo ri = p.reqs[r];
-    for (int u = threadIdx.x; u < total; u += AWG) {
+    for (int u = tid; u < total; u += AWG) {
         const int row = first_row + u / cpt, rem = u % cpt;
         while (row >= ri.row_off + ri.L) ri = p.reqs[++r];   // (requests with L = 0 are stepped over)
         const int h = rem / cph, ch = rem % cph;
@@ -936,16 +936,16 @@ __device__ __forceinline__ int steal_item(const AttnParams& p) {
 }
 
 template <int D, int KVT>
-__device__ __forceinline__ void run_item(const AttnParams& p, int idx, uint32_t smem) {
+__device__ __forceinline__ void run_item(const AttnParams& p, int idx, uint32_t smem, int tid) {
     const int kind = (p.items[idx].heads >> 24) & 0xff;
     if (kind == KIND_NULL) return;                         // a filler that keeps the following items on their XCD
     const ItemCtx ic = load_item(p, idx);
     if (kind == KIND_WIDE)
-        wide_body<D, KVT>(p, ic, smem);
+        wide_body<D, KVT>(p, ic, smem, tid);
     else if (kind == KIND_NARROW)
-        narrow_body<D, KVT>(p, ic, smem);
+        narrow_body<D, KVT>(p, ic, smem, tid);
     else if (KVT == KV_BF16)
-        append_body(p, ic, D);
+        append_body(p, ic, D, tid);
 }
 
 // One workgroup per work item when the items fit one round on the CUs (gridDim.x = number of items).  Otherwise
@@ -961,23 +961,27 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
     const uint32_t smem = (uint32_t)(uintptr_t)LDS_PTR(char, smem_raw);
     if (blockIdx.x == 0 && threadIdx.x == 0 && p.slot_flag)   // releases the host's staging slot (see AttnParams)
         __hip_atomic_store(p.slot_flag, p.slot_seq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
-    if (p.nitems <= (int)gridDim.x) {
-        run_item<D, KVT>(p, blockIdx.x, smem);
-        return;
-    }
+    const bool persistent = p.nitems > (int)gridDim.x;
     const int home = blockIdx.x % NUM_QUEUES;
     int idx = blockIdx.x;
     for (;;) {
-        run_item<D, KVT>(p, idx, smem);
-        __syncthreads();                                   // every wave is done with this item's LDS (and has read s_next)
-        if (threadIdx.x == 0) {
-            // taken when the item is done, not before: the queues are ordered longest first, and an item reserved
-            // early would go to a workgroup by its position in the launch instead of to the one that is free first
+        // The thread index is made opaque in every iteration: otherwise everything the three kinds of item derive from it
+        // is hoisted out of the loop and live at once, which does not fit the register file (spills to scratch memory).
+        int tid = threadIdx.x;
+        asm volatile("" : "+v"(tid));
+        run_item<D, KVT>(p, idx, smem, tid);
+        if (!persistent) return;
+        __syncthreads();                                   // every wave is done with this item's LDS
+        if (tid == 0) {
+            // The next item is taken when this one is done, not before (measured: a reservation at the start of the item
+            // +5 % on long tiles, one during its last stage +1 %): the queues are ordered longest first, and an item
+            // reserved early goes to a workgroup by its position in the launch instead of to the one that is free first.
             const int next = take_item(p, home);
             s_next = next >= 0 ? next : steal_item(p);
         }
         __syncthreads();
-        idx = s_next;
+        idx = __builtin_amdgcn_readfirstlane(s_next);      // uniform: the item is then read through the scalar unit
+        __syncthreads();                                   // (s_next is written again at the end of the next item)
         if (idx < 0) return;
     }
 }
