@@ -915,21 +915,29 @@ __device__ __forceinline__ int take_item(const AttnParams& p, int q) {
     const int idx = q + NUM_QUEUES * pos;
     return idx < p.nitems ? idx : -1;
 }
-// An item of the queue with the most items left, or -1 when every queue is used up (bounded: every failed
-// attempt means another workgroup took the item).
-__device__ __forceinline__ int steal_item(const AttnParams& p) {
+// An item of the queue with the most items left, or -1 when every queue is used up.  Called by the whole first wave: lanes
+// 0 .. NUM_QUEUES - 1 read one queue head each (one round trip for the scan), lane 0 takes the item.  Bounded: an attempt
+// fails only when another workgroup took the last item of the chosen queue in between, and that workgroup runs it.
+__device__ __forceinline__ int steal_item(const AttnParams& p, int lane) {
     for (int attempt = 0; attempt < 4 * NUM_QUEUES; ++attempt) {
+        int left = 0;
+        if (lane < NUM_QUEUES) {
+            const int pos = __hip_atomic_load(p.queue_heads + lane, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            left = (p.nitems - lane + NUM_QUEUES - 1) / NUM_QUEUES - pos;
+        }
         int best = -1, best_left = 0;
+#pragma unroll
         for (int q = 0; q < NUM_QUEUES; ++q) {
-            const int pos = __hip_atomic_load(p.queue_heads + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            const int left = (p.nitems - q + NUM_QUEUES - 1) / NUM_QUEUES - pos;
-            if (left > best_left) {
-                best_left = left;
+            const int l = __builtin_amdgcn_readlane(left, q);
+            if (l > best_left) {
+                best_left = l;
                 best = q;
             }
         }
         if (best < 0) return -1;
-        const int idx = take_item(p, best);
+        int idx = -1;
+        if (lane == 0) idx = take_item(p, best);
+        idx = __builtin_amdgcn_readfirstlane(idx);
         if (idx >= 0) return idx;
     }
     return -1;
@@ -972,12 +980,15 @@ __global__ __launch_bounds__(AWG, 1) void attn_kernel(const AttnParams p) {
         run_item<D, KVT>(p, idx, smem, tid);
         if (!persistent) return;
         __syncthreads();                                   // every wave is done with this item's LDS
-        if (tid == 0) {
+        if (tid < 64) {
             // The next item is taken when this one is done, not before (measured: a reservation at the start of the item
             // +5 % on long tiles, one during its last stage +1 %): the queues are ordered longest first, and an item
             // reserved early goes to a workgroup by its position in the launch instead of to the one that is free first.
-            const int next = take_item(p, home);
-            s_next = next >= 0 ? next : steal_item(p);
+            int next = -1;
+            if (tid == 0) next = take_item(p, home);
+            next = __builtin_amdgcn_readfirstlane(next);
+            if (next < 0) next = steal_item(p, tid);
+            if (tid == 0) s_next = next;
         }
         __syncthreads();
         idx = __builtin_amdgcn_readfirstlane(s_next);      // uniform: the item is then read through the scalar unit

@@ -392,7 +392,7 @@ void build_plan(const Shape& s, int num_reqs, const int32_t* ctx_len, const int3
     out.off_queues = out.off_combs + round_up((int64_t)out.combs.size() * sizeof(CombItem), 256);
     out.plan_bytes = out.off_queues + 256;
     // persistent workgroups pay off where tiles are in the launch (the dies finish together: -1.2 % on configuration 2, -3.5 % on
-    // the fused mixed launch of configuration 3); a launch of decode rows alone is 6 % faster with one workgroup per item
+    // the fused mixed launch of configuration 3); a launch of decode rows alone gains nothing from them (+-1 %)
     out.grid = (int32_t)(out.num_wide > 0 ? std::min<int64_t>((int64_t)out.items.size(), opt.wg_slots) : (int64_t)out.items.size());
     for (int q = 0; q < NUM_QUEUES; ++q) out.queue_heads[q] = out.grid > q ? (out.grid - q + NUM_QUEUES - 1) / NUM_QUEUES : 0;
     out.off_partial = out.plan_bytes;
