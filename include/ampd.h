@@ -230,6 +230,8 @@ typedef struct {
     int64_t partial_bytes;      /* split-KV partial results inside the workspace */
     int64_t plan_bytes;         /* work list inside the workspace */
     int64_t num_append_items;   /* bf16 cache: page-write items (64 packed rows each) that close the attention launch */
+    int64_t num_workgroups;     /* workgroups of the attention launch: num_items, or 256 persistent workgroups that work
+                                 * through the items when the launch holds tiles and more items than that */
 } ampd_plan_info;
 ampd_status ampd_plan_describe(const ampd_kv_cache *cache, const ampd_batch *batch,
                                const ampd_plan_options *opts, ampd_plan_info *info);

@@ -53,7 +53,7 @@ class _Opts(ctypes.Structure):
 class _PlanInfo(ctypes.Structure):
     _fields_ = [(n, ctypes.c_int64) for n in ("num_items", "num_wide_items", "num_narrow_items",
                                               "num_combine_items", "num_append_launches",
-                                              "partial_bytes", "plan_bytes", "num_append_items")]
+                                              "partial_bytes", "plan_bytes", "num_append_items", "num_workgroups")]
 
 
 HOST_ONLY_SYMBOLS = ["ampd_workspace_bytes", "ampd_workspace_bytes_opts", "ampd_plan_describe", "ampd_plan_items",

@@ -137,6 +137,7 @@ ampd_status ampd_plan_describe(const ampd_kv_cache* cache, const ampd_batch* bat
     info->num_append_launches = plan.num_append > 0 ? 0 : (batch->num_reqs + APPEND_MAX_REQS - 1) / APPEND_MAX_REQS;
     info->partial_bytes = plan.partial_floats * 4;
     info->plan_bytes = plan.plan_bytes;
+    info->num_workgroups = plan.grid;
     return AMPD_OK;
 }
 

@@ -209,6 +209,24 @@ def test_planner_narrow_chunks_follow_the_number_of_workgroup_slots():
     assert k1.max() == 256 and len(a1) == 4 * 8 * 3
 
 
+def test_planner_launch_shape_persistent_workgroups_only_for_long_lists_with_tiles():
+    """A launch with tiles and more items than CUs is run by 256 persistent workgroups; decode rows alone, and everything
+    that fits one round, get one workgroup per item."""
+    c2 = shape_cache(32, 8, 128, 16)
+    C, L = W.config_lengths(2)
+    info = A.plan_describe(c2, C, L, int(((C.astype(int) + L + 15) // 16).max()))
+    assert info["num_items"] > 256 and info["num_wide_items"] > 0 and info["num_workgroups"] == 256
+    c3 = shape_cache(64, 8, 128, 16)
+    C, L = W.config_lengths(3, part="decode")
+    info = A.plan_describe(c3, C, L, int(((C.astype(int) + L + 15) // 16).max()))
+    assert info["num_wide_items"] == 0 and info["num_workgroups"] == info["num_items"] == 770
+    C, L = W.config_lengths(3)
+    info = A.plan_describe(c3, C, L, int(((C.astype(int) + L + 15) // 16).max()))
+    assert info["num_workgroups"] == 256
+    info = A.plan_describe(c2, np.array([700], np.int32), np.array([100], np.int32), 60)
+    assert info["num_workgroups"] == info["num_items"] <= 256
+
+
 def test_planner_cuts_the_tiles_of_a_small_prefill_for_one_round():
     """A single incremental prefill (the paper's T_pre(l_hist, l_incr) case) has fewer tiles than workgroup slots: the key
     ranges of its tiles are cut so that the pieces fit one round on the 256 slots (all, half or a quarter of them), in
