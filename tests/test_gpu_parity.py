@@ -123,13 +123,15 @@ def test_lone_prefill_whose_tiles_the_planner_cuts_for_one_round(C, L):
 
 
 def test_seeded_batches_in_the_regimes_of_the_split_policy():
-    """Thirty-six seeded random batches, six in each regime in which the planner cuts key ranges differently: a lone
-    prefill (tiles cut for one round), a few long decode rows (one round of key ranges), a decode batch with one to three
-    blocks per workgroup slot, decode rows next to a prefill row, a small ragged batch, several prefill rows; head
-    geometry (odd group sizes included), head dim and page size drawn as well, some with forced splits."""
+    """Forty-eight seeded random batches, six in each regime in which the planner cuts key ranges or shapes the launch
+    differently: a lone prefill (tiles cut for one round), a few long decode rows (one round of key ranges), a decode batch
+    with one to three blocks per workgroup slot, decode rows next to a prefill row, a small ragged batch, several prefill
+    rows, many prefill rows and large mixed batches (long work lists with tiles: persistent workgroups that take items
+    from their die's queue and from other dies'); head geometry (odd group sizes included), head dim and page size drawn
+    as well, some with forced splits."""
     rng = np.random.default_rng(20260215)
-    for case in range(36):
-        regime = case % 6
+    for case in range(48):
+        regime = case % 8
         Hkv = int(rng.choice([1, 2, 8])); G = int(rng.choice([1, 3, 4, 5, 8, 16])); d = int(rng.choice([64, 128])); P = int(rng.choice([16, 32]))
         if regime == 0:
             C = [int(rng.integers(0, 20000))]; L = [int(rng.integers(33, 1500))]
@@ -145,8 +147,14 @@ def test_seeded_batches_in_the_regimes_of_the_split_policy():
             n = int(rng.integers(1, 8)); C = [int(rng.integers(0, 1200)) for _ in range(n)]; L = [int(rng.integers(0, 300)) for _ in range(n)]
             if sum(L) == 0:
                 L[0] = 3
-        else:
+        elif regime == 5:
             n = int(rng.integers(2, 6)); C = [int(rng.integers(0, 5000)) for _ in range(n)]; L = [int(rng.integers(40, 700)) for _ in range(n)]
+        elif regime == 6:
+            n = int(rng.integers(6, 15)); C = [int(rng.integers(0, 4000)) for _ in range(n)]; L = [int(rng.integers(100, 900)) for _ in range(n)]
+        else:
+            n = int(rng.integers(30, 80)); C = [int(rng.integers(100, 3000)) for _ in range(n)]; L = [1] * n
+            for _ in range(int(rng.integers(3, 8))):
+                C.append(int(rng.integers(0, 3000))); L.append(int(rng.integers(64, 700)))
         if Hkv * G * d * sum(c + l for c, l in zip(C, L)) > 6e8:          # bound the host-side pool
             Hkv = 1
         splits = int(rng.choice([0, 0, 0, 2, 7]))
