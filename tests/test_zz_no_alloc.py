@@ -71,3 +71,31 @@ def test_static_workspace_entry_point_rejects_what_does_not_fit(name, n, c, l, H
     assert ei.value.status == -3                      # AMPD_ERR_WORKSPACE
     torch.cuda.synchronize()
     assert not pool.any(), "a rejected call must not have enqueued the append"
+
+
+def test_static_entry_point_waits_for_the_oldest_staging_buffer_when_all_are_in_flight():
+    """The entry point may not pin another staging buffer, so with all buffers of the ring in flight it waits until the
+    attention launch of the oldest call has started.  Far more calls than buffers are enqueued back to back, each long
+    enough on the GPU for the host to run ahead; every call must come back (in bounded time), and the last output must
+    equal that of the workspace entry point bit for bit."""
+    import time
+    print("case: static workspace, calls in flight beyond the ring", flush=True)
+    A.init()
+    b = W.make_batch([3000, 2500, 3500, 2800], [400, 380, 420, 390], 32, 8, 128, 16, seed=73, poison=True)
+    ref_db, st_db = DevBatch(b), DevBatch(b)
+    ref = A.mixed_batch_attn(ref_db.cache, b.ctx_len, b.incr_len, ref_db.bt, ref_db.q, ref_db.k_new, ref_db.v_new,
+                             block_table_host=b.block_table)
+    outs = [torch.full_like(st_db.q, float("nan")) for _ in range(4)]
+    torch.cuda.synchronize()
+    calls = 400
+    t0 = time.perf_counter()
+    for i in range(calls):
+        A.mixed_batch_attn_static(st_db.cache, b.ctx_len, b.incr_len, st_db.bt, st_db.q, st_db.k_new, st_db.v_new,
+                                  outs[i % 4], block_table_host=b.block_table)
+    host_s = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    print(f"{calls} calls: host {host_s * 1e3:.1f} ms, with the GPU {total_s * 1e3:.1f} ms", flush=True)
+    assert total_s < 2.0, "a call waited for its staging buffer far longer than the GPU work takes"
+    for o in outs:
+        assert np.array_equal(from_dev_bits(o), from_dev_bits(ref))
