@@ -223,3 +223,43 @@ def test_many_calls_in_flight_never_wait_for_the_gpu():
     assert max(host) < 0.25 * t_gpu, "one call took a large part of the whole sequence"
     for i in range(1, ncalls):
         assert torch.equal(outs[i], outs[0])
+
+
+def test_two_host_threads_on_two_streams_share_the_library():
+    """Two host threads, each with its own stream, workspace and batch, call the library at the same time (ctypes releases
+    the interpreter lock during a call): the staging ring and its sequence numbers are shared under a mutex, the last
+    plan is kept per thread.  Every output must equal the single-threaded result of its batch bit for bit."""
+    import threading
+    print("case: two host threads", flush=True)
+    batches = [W.make_batch([900, 40, 2000], [130, 1, 260], 16, 4, 128, 16, seed=91, poison=True),
+               W.make_batch([3000, 3100, 2900, 5], [1, 1, 1, 70], 16, 4, 128, 16, seed=92, poison=True)]
+    refs = [run(DevBatch(b)) for b in batches]
+    dbs = [DevBatch(b) for b in batches]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    ncalls = 60
+    outs = [[torch.empty_like(db.q) for _ in range(ncalls)] for db in dbs]
+    wss = [torch.empty(A.workspace_bytes(db.cache, b.ctx_len, b.incr_len, db.bt.shape[1]), dtype=torch.uint8, device="cuda")
+           for db, b in zip(dbs, batches)]
+    errors = []
+    torch.cuda.synchronize()
+
+    def worker(t):
+        try:
+            b, db = batches[t], dbs[t]
+            for i in range(ncalls):
+                A.mixed_batch_attn(db.cache, b.ctx_len, b.incr_len, db.bt, db.q, db.k_new, db.v_new, out=outs[t][i],
+                                   workspace=wss[t], stream=streams[t])
+            streams[t].synchronize()
+        except Exception as e:            # noqa: BLE001 (reported by the main thread)
+            errors.append(e)
+
+    threads = [threading.Thread(target=worker, args=(t,)) for t in range(2)]
+    for th in threads:
+        th.start()
+    for th in threads:
+        th.join()
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for t in range(2):
+        for i in range(ncalls):
+            assert np.array_equal(from_dev_bits(outs[t][i]), refs[t]), f"thread {t} call {i}"
