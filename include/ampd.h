@@ -29,6 +29,9 @@
  *     flight (at 4096 buffers a call waits for the oldest instead).  The one exception is
  *     ampd_mixed_batch_attn_static, which may not allocate and waits for the oldest buffer.
  *   - HOST arrays are read before the call returns and may be reused immediately.
+ *   - Threads: every entry point may be called from several host threads at once (the staging
+ *     ring is shared under a lock; the last work list is kept per thread).  Calls that use the
+ *     same workspace, output or pages must be ordered by the caller (same stream, or events).
  *
  * Layouts
  *   - Pools:  k_pool, v_pool  [num_pages][Hkv][P][d]  (row-major, bf16 bit patterns, or
