@@ -455,7 +455,19 @@ struct Loader {
     static constexpr int ES = RawChunk<KVT>::ES;
     int pg[NPASS];
     RawChunk<KVT> k[NPASS], v[NPASS];
-    float ks[NPASS], vs[NPASS];
+    // 8-bit cache: the page scales of the tile.  One per pass in general; the one-wave loader of narrow items (32 keys from a
+    // multiple of 32) sees at most two pages (page size >= 16), and keeps two scales instead of eight per operand.
+    static constexpr bool TWO_SCALES = NW == 1 && NKEYS == 32;
+    static constexpr int NSC = TWO_SCALES ? 2 : NPASS;
+    float ks[NSC], vs[NSC];
+    __device__ __forceinline__ float k_scale_of(const AttnParams& p, int ps) const {
+        if constexpr (TWO_SCALES) return ps * KPW < p.P ? ks[0] : ks[1];
+        else return ks[ps];
+    }
+    __device__ __forceinline__ float v_scale_of(const AttnParams& p, int ps) const {
+        if constexpr (TWO_SCALES) return ps * KPW < p.P ? vs[0] : vs[1];
+        else return vs[ps];
+    }
 
     // t: thread index inside the group of NTHR threads.  The block table is read through the
     // scalar cache (it is constant for the duration of the kernel): scalar loads do not count
@@ -528,11 +540,16 @@ struct Loader {
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
             const Row r = row_of(p, ic, kbase, t, ps);
-            ks[ps] = 1.0f;
-            vs[ps] = 1.0f;
-            if (KVT == KV_FP8 && (FULL || r.key0 < ic.kv_end)) {   // (a group past the key range has no page)
-                ks[ps] = p.k_scale[(int64_t)r.page * p.Hkv + ic.kvh];
-                vs[ps] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
+            // the scale slot this pass fills: its own, or (two scales) slot 0 from the first pass and slot 1 from the pass
+            // of key 16, the first of the second page when pages hold 16 keys (with larger pages slot 1 is never read)
+            const int sl = !TWO_SCALES ? ps : ps == 0 ? 0 : ps == 16 / KPW ? 1 : -1;
+            if (sl >= 0) {
+                ks[sl] = 1.0f;
+                vs[sl] = 1.0f;
+                if (KVT == KV_FP8 && (FULL || r.key0 < ic.kv_end)) {   // (a group past the key range has no page)
+                    ks[sl] = p.k_scale[(int64_t)r.page * p.Hkv + ic.kvh];
+                    vs[sl] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
+                }
             }
             const int key = r.key0 + ((t & 63) >> 2) % KPW;
             if (FULL || (key < ic.kv_end && key < ic.c_rows)) {
@@ -556,12 +573,12 @@ struct Loader {
             fetch_kv_impl<false>(p, ic, kbase, t);
     }
     // kl / vl: LDS byte addresses of this tile's K and V
-    __device__ __forceinline__ void commit(uint32_t kl, uint32_t vl, int t) const {
+    __device__ __forceinline__ void commit(const AttnParams& p, uint32_t kl, uint32_t vl, int t) const {
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
             const uint32_t o = (ps * NW + (t >> 6)) * G_::GS + (t & 63) * 16;
-            *LDS_PTR(u32x4, kl + o) = k[ps].widen(ks[ps]);
-            *LDS_PTR(u32x4, vl + o) = v[ps].widen(vs[ps]);
+            *LDS_PTR(u32x4, kl + o) = k[ps].widen(k_scale_of(p, ps));
+            *LDS_PTR(u32x4, vl + o) = v[ps].widen(v_scale_of(p, ps));
         }
     }
 
@@ -729,7 +746,7 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
         ld.fetch_pages(p, ic, k_lo, tid);
         ld.fetch_kv(p, ic, k_lo, tid);
         if (ntiles > 1) ld.fetch_pages(p, ic, k_lo + KT, tid);
-        ld.commit(smem, smem + G_::KTILE, tid);
+        ld.commit(p, smem, smem + G_::KTILE, tid);
         __syncthreads();
         auto step = [&](int t, auto masked) {
             const uint32_t cur = smem + (t & 1) * G_::WIDE_STAGE;
@@ -740,7 +757,7 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
                 if (t + 2 < ntiles) ld.fetch_pages(p, ic, k_lo + (t + 2) * KT, tid);
             }
             compute(t, cur, masked);
-            if (more) ld.commit(nxt, nxt + G_::KTILE, tid);
+            if (more) ld.commit(p, nxt, nxt + G_::KTILE, tid);
             __syncthreads();
         };
         for (int t = 0; t < t_diag; ++t) step(t, std::false_type{});
@@ -783,7 +800,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
     }
     for (int b = wave; b < nblocks; b += ATTN_WAVES) {
         const int kbase = ic.kv_begin + b * 32;
-        ld.commit(kl, vl, lane);
+        ld.commit(p, kl, vl, lane);
         if (b + ATTN_WAVES < nblocks) {
             ld.fetch_kv(p, ic, kbase + 32 * ATTN_WAVES, lane);
             if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
