@@ -106,23 +106,25 @@ struct RawChunk<KV_BF16> {
 };
 template <>
 struct RawChunk<KV_FP8> {
-    u32x2 v;
+    u32x4 v;                                          // 16 codes: two neighbouring chunks of one key row
     static constexpr int ES = 1;
-    __device__ __forceinline__ void zero() { v = u32x2{0, 0}; }
+    __device__ __forceinline__ void zero() { v = u32x4{0, 0, 0, 0}; }
     __device__ __forceinline__ void load(const char* base, uint32_t lane_off) {
-        v = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(base + lane_off));
+        v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(base + lane_off));
     }
     // decode(code) * scale is exact in bf16: 4 significant bits times a power of two.  The page scales are
     // powers of two (the append kernel writes no others), so the hardware's scaled conversion, which applies
     // the exponent of `scale` only, is that product: one instruction per two elements.
-    __device__ __forceinline__ u32x4 widen(float scale) const {
-        const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, scale, false);
-        const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.x, scale, true);
-        const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, scale, false);
-        const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(v.y, scale, true);
+    __device__ __forceinline__ static u32x4 widen8(uint32_t lo, uint32_t hi, float scale) {
+        const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, scale, false);
+        const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(lo, scale, true);
+        const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, false);
+        const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(hi, scale, true);
         return u32x4{__builtin_bit_cast(uint32_t, a), __builtin_bit_cast(uint32_t, b), __builtin_bit_cast(uint32_t, c),
                      __builtin_bit_cast(uint32_t, d)};
     }
+    __device__ __forceinline__ u32x4 widen_first(float scale) const { return widen8(v.x, v.y, scale); }
+    __device__ __forceinline__ u32x4 widen_second(float scale) const { return widen8(v.z, v.w, scale); }
 };
 
 struct ItemCtx {
@@ -451,7 +453,13 @@ struct Loader {
     static constexpr int KPW = G_::KPW;
     static constexpr int NGRP = NKEYS / KPW;          // groups per tile
     static constexpr int NW = NTHR / 64;              // cooperating waves
-    static constexpr int NPASS = NGRP / NW;
+    // 8-bit cache: a wave moves two consecutive groups per pass, 16 codes per lane (lanes 0-31 the first group, 32-63 the
+    // second; a lane fills two neighbouring LDS slots): half as many loads and address computations per byte as with
+    // one 8-byte chunk per lane.  Two groups are 8 or 16 keys from a multiple of that, so they share a page too.
+    static constexpr int GPP = KVT == KV_FP8 ? 2 : 1; // groups per wave and pass
+    static constexpr int KPP = GPP * KPW;             // keys per wave and pass
+    static constexpr int NPASS = NGRP / (NW * GPP);
+    static_assert(NPASS >= 1 && NPASS * NW * GPP == NGRP, "tile, waves and passes");
     static constexpr int ES = RawChunk<KVT>::ES;
     int pg[NPASS];
     RawChunk<KVT> k[NPASS], v[NPASS];
@@ -461,11 +469,11 @@ struct Loader {
     static constexpr int NSC = TWO_SCALES ? 2 : NPASS;
     float ks[NSC], vs[NSC];
     __device__ __forceinline__ float k_scale_of(const AttnParams& p, int ps) const {
-        if constexpr (TWO_SCALES) return ps * KPW < p.P ? ks[0] : ks[1];
+        if constexpr (TWO_SCALES) return ps * KPP < p.P ? ks[0] : ks[1];
         else return ks[ps];
     }
     __device__ __forceinline__ float v_scale_of(const AttnParams& p, int ps) const {
-        if constexpr (TWO_SCALES) return ps * KPW < p.P ? vs[0] : vs[1];
+        if constexpr (TWO_SCALES) return ps * KPP < p.P ? vs[0] : vs[1];
         else return vs[ps];
     }
 
@@ -480,7 +488,7 @@ struct Loader {
         const int w = __builtin_amdgcn_readfirstlane(t >> 6);
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
-            const int key0 = kbase + (ps * NW + w) * KPW;
+            const int key0 = kbase + (ps * NW + w) * KPP;
             pg[ps] = key0 < ic.kv_end ? bt[key0 >> p.logP] : 0;
         }
     }
@@ -491,7 +499,7 @@ struct Loader {
     // in order behind the direct loads of the same step, and the wait that ends the step covers them.
     int pgv;
     __device__ __forceinline__ void fetch_pages_v(const AttnParams& p, const ItemCtx& ic, int kbase, int t) {
-        const int key0 = kbase + (((t & 63) % NPASS) * NW + (t >> 6)) * KPW;
+        const int key0 = kbase + (((t & 63) % NPASS) * NW + (t >> 6)) * KPP;
         pgv = key0 < ic.kv_end ? ic.bt_row[key0 >> p.logP] : 0;
     }
     __device__ __forceinline__ void take_pages() {
@@ -499,9 +507,14 @@ struct Loader {
         for (int ps = 0; ps < NPASS; ++ps) pg[ps] = __builtin_amdgcn_readlane(pgv, ps);
     }
 
+    // The lane's first LDS slot inside its group, and which of the pass's groups that is.  Slot l = (quad, key, chunk in
+    // quad); with two groups per pass a lane owns slots l and l + 1 (l even: neighbouring chunks of one key row).
+    __device__ __forceinline__ static int lane_slot(int t) { return GPP == 1 ? (t & 63) : 2 * (t & 31); }
+    __device__ __forceinline__ static int lane_group(int t) { return GPP == 1 ? 0 : (t & 63) >> 5; }
+    __device__ __forceinline__ static int lane_key(int t) { return lane_group(t) * KPW + (lane_slot(t) >> 2) % KPW; }   // within the pass
     __device__ __forceinline__ static uint32_t lane_off(int t) {
-        const int l = t & 63;                          // LDS slot l = (quad, key, chunk in quad)
-        return (uint32_t)((((l >> 2) % KPW) * D + ((l / (4 * KPW)) * 4 + (l & 3)) * 8) * ES);
+        const int l = lane_slot(t);
+        return (uint32_t)((lane_key(t) * D + ((l / (4 * KPW)) * 4 + (l & 3)) * 8) * ES);
     }
 
     struct Row {
@@ -510,7 +523,7 @@ struct Loader {
     };
     __device__ __forceinline__ Row row_of(const AttnParams& p, const ItemCtx& ic, int kbase, int t, int ps) const {
         Row r;
-        r.key0 = __builtin_amdgcn_readfirstlane(kbase + (ps * NW + (t >> 6)) * KPW);
+        r.key0 = __builtin_amdgcn_readfirstlane(kbase + (ps * NW + (t >> 6)) * KPP);
         r.page = __builtin_amdgcn_readfirstlane(pg[ps]);
         const int64_t row = ((((int64_t)r.page * p.Hkv + ic.kvh) << p.logP) + (r.key0 & (p.P - 1))) * D * ES;
         r.kb = static_cast<const char*>(p.k_pool) + row;
@@ -542,7 +555,7 @@ struct Loader {
             const Row r = row_of(p, ic, kbase, t, ps);
             // the scale slot this pass fills: its own, or (two scales) slot 0 from the first pass and slot 1 from the pass
             // of key 16, the first of the second page when pages hold 16 keys (with larger pages slot 1 is never read)
-            const int sl = !TWO_SCALES ? ps : ps == 0 ? 0 : ps == 16 / KPW ? 1 : -1;
+            const int sl = !TWO_SCALES ? ps : ps == 0 ? 0 : ps == 16 / KPP ? 1 : -1;
             if (sl >= 0) {
                 ks[sl] = 1.0f;
                 vs[sl] = 1.0f;
@@ -551,7 +564,7 @@ struct Loader {
                     vs[sl] = p.v_scale[(int64_t)r.page * p.Hkv + ic.kvh];
                 }
             }
-            const int key = r.key0 + ((t & 63) >> 2) % KPW;
+            const int key = r.key0 + lane_key(t);
             if (FULL || (key < ic.kv_end && key < ic.c_rows)) {
                 k[ps].load(r.kb, lo);
                 v[ps].load(r.vb, lo);
@@ -576,9 +589,16 @@ struct Loader {
     __device__ __forceinline__ void commit(const AttnParams& p, uint32_t kl, uint32_t vl, int t) const {
 #pragma unroll
         for (int ps = 0; ps < NPASS; ++ps) {
-            const uint32_t o = (ps * NW + (t >> 6)) * G_::GS + (t & 63) * 16;
-            *LDS_PTR(u32x4, kl + o) = k[ps].widen(k_scale_of(p, ps));
-            *LDS_PTR(u32x4, vl + o) = v[ps].widen(v_scale_of(p, ps));
+            const uint32_t o = ((ps * NW + (t >> 6)) * GPP + lane_group(t)) * G_::GS + lane_slot(t) * 16;
+            if constexpr (KVT == KV_FP8) {
+                *LDS_PTR(u32x4, kl + o) = k[ps].widen_first(k_scale_of(p, ps));
+                *LDS_PTR(u32x4, kl + o + 16) = k[ps].widen_second(k_scale_of(p, ps));
+                *LDS_PTR(u32x4, vl + o) = v[ps].widen_first(v_scale_of(p, ps));
+                *LDS_PTR(u32x4, vl + o + 16) = v[ps].widen_second(v_scale_of(p, ps));
+            } else {
+                *LDS_PTR(u32x4, kl + o) = k[ps].widen(k_scale_of(p, ps));
+                *LDS_PTR(u32x4, vl + o) = v[ps].widen(v_scale_of(p, ps));
+            }
         }
     }
 
@@ -592,7 +612,7 @@ struct Loader {
             const Row r = row_of(p, ic, kbase, t, ps);
             // wave-uniform LDS offset of the group
             const uint32_t go = __builtin_amdgcn_readfirstlane((ps * NW + (t >> 6)) * G_::GS);
-            const int key = r.key0 + ((t & 63) >> 2) % KPW;
+            const int key = r.key0 + lane_key(t);
             if (FULL || (key < ic.kv_end && key < ic.c_rows)) {
                 dma16(r.kb, lo, __builtin_amdgcn_readfirstlane(kl) + go);
                 dma16(r.vb, lo, __builtin_amdgcn_readfirstlane(vl) + go);
