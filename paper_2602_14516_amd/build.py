@@ -40,6 +40,32 @@ def build(force: bool = False, verbose: bool = False) -> str:
     return LIB
 
 
+def kernel_resources() -> dict:
+    """Registers, scratch and LDS of every kernel in kernels.hip, as the compiler reports them for gfx950
+    (-Rpass-analysis=kernel-resource-usage; device code only, nothing is linked or written next to the sources)."""
+    import re
+    import tempfile
+    with tempfile.TemporaryDirectory() as tmp:
+        cmd = [HIPCC, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+               "-I", INCLUDE, "-I", CSRC, "-c", "--cuda-device-only", "-Rpass-analysis=kernel-resource-usage",
+               os.path.join(CSRC, "kernels.hip"), "-o", os.path.join(tmp, "kernels.o")]
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + res.stdout)
+    out, name = {}, None
+    for line in res.stdout.splitlines():
+        m = re.search(r"remark:\s+(Function Name|VGPRs|AGPRs|TotalSGPRs|ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill|"
+                      r"LDS Size \[bytes/block\]|Occupancy \[waves/SIMD\]): (\S+)", line)
+        if not m:
+            continue
+        if m.group(1) == "Function Name":
+            name = m.group(2)
+            out[name] = {}
+        elif name is not None:
+            out[name][m.group(1)] = int(m.group(2))
+    return out
+
+
 SCHED_LIB = os.path.join(HERE, "libampd_sched.so")
 SCHED_SRC = os.path.join(CSRC, "sched.cpp")
 SCHED_HDR = os.path.join(INCLUDE, "ampd_sched.h")
