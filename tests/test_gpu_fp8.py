@@ -184,6 +184,83 @@ def test_seeded_random_fp8_rounds():
             C = (C + L).astype(np.int32)
 
 
+@pytest.mark.timeout(900)
+def test_seeded_fp8_batches_in_every_planner_regime():
+    """Eighteen seeded batches over an 8-bit cache, three in each regime in which the planner shapes the launch differently
+    (a lone prefill over history, a few long decode rows, a decode batch, decode rows next to prefill rows, a small ragged
+    batch, many prefill rows: persistent workgroups); head geometry (odd group sizes included), head dim and page size
+    drawn as well, some with forced splits.  The history is written by a first call (pools bit-exact after it), the
+    batch itself by a second: pools bit-exact again, attention against the oracle on the dequantised cache at the bf16
+    tolerance."""
+    rng = np.random.default_rng(20260216)
+    for case in range(18):
+        regime = case % 6
+        Hkv = int(rng.choice([1, 2, 8])); G = int(rng.choice([1, 3, 4, 5, 8, 16])); d = int(rng.choice([64, 128])); P = int(rng.choice([16, 32]))
+        if regime == 0:
+            C = [int(rng.integers(0, 9000))]; L = [int(rng.integers(33, 500))]
+        elif regime == 1:
+            n = int(rng.integers(1, 6)); C = [int(rng.integers(2000, 16000)) for _ in range(n)]; L = [1] * n
+        elif regime == 2:
+            n = int(rng.integers(20, 70)); C = [int(rng.integers(100, 3000)) for _ in range(n)]; L = [1] * n
+        elif regime == 3:
+            n = int(rng.integers(4, 30)); C = [int(rng.integers(100, 4000)) for _ in range(n)]; L = [1] * n
+            for _ in range(int(rng.integers(1, 3))):
+                C.append(int(rng.integers(0, 4000))); L.append(int(rng.integers(2, 400)))
+        elif regime == 4:
+            n = int(rng.integers(1, 8)); C = [int(rng.integers(0, 1200)) for _ in range(n)]; L = [int(rng.integers(0, 300)) for _ in range(n)]
+            if sum(L) == 0:
+                L[0] = 3
+        else:
+            n = int(rng.integers(6, 12)); C = [int(rng.integers(0, 2500)) for _ in range(n)]; L = [int(rng.integers(100, 500)) for _ in range(n)]
+        if Hkv * G * d * sum(c + l for c, l in zip(C, L)) > 1.5e8:            # bound the host-side reference work
+            Hkv = 1
+        if Hkv * G * d * sum(c + l for c, l in zip(C, L)) > 1.5e8:
+            G = min(G, 4)
+        Hq, B = Hkv * G, len(C)
+        splits = int(rng.choice([0, 0, 0, 2, 7]))
+        print(f"case {case}: regime {regime} Hq={Hq} Hkv={Hkv} d={d} P={P} n={B} sum C={sum(C)} sum L={sum(L)} splits={splits}", flush=True)
+        C, L = np.array(C, np.int32), np.array(L, np.int32)
+        pages = (C.astype(np.int64) + L + P - 1) // P
+        num_pages = int(pages.sum()) + 3
+        perm = rng.permutation(num_pages).astype(np.int32)
+        bt = np.full((B, max(1, int(pages.max()))), -1, np.int32)
+        o = 0
+        for r in range(B):
+            bt[r, :pages[r]] = perm[o:o + pages[r]]; o += pages[r]
+        scale = 1.0 / np.sqrt(d)
+        pool = Fp8Pool(num_pages, Hq, Hkv, d, P, scale)
+        d_bt = torch.from_numpy(bt).cuda()
+        have = np.zeros(B, np.int32)
+        for step, Ls in enumerate((C, L)):
+            n = int(Ls.sum())
+            if n > 0:
+                mag = np.exp2(rng.integers(-2, 1, size=(n, Hkv, 1))).astype(np.float32)
+                q = W.f32_to_bf16_bits(rng.standard_normal((n, Hq, d), dtype=np.float32))
+                k = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, d), dtype=np.float32) * mag * (0.5 + step))
+                v = W.f32_to_bf16_bits(rng.standard_normal((n, Hkv, d), dtype=np.float32) * mag)
+                fn = A.mixed_batch_attn if case % 2 else A.incr_prefill_attn
+                out = fn(pool.cache, have, Ls, d_bt, to_dev_bits(q), to_dev_bits(k), to_dev_bits(v), block_table_host=bt,
+                         force_kv_splits=splits if step == 1 else 0)
+                torch.cuda.synchronize()
+                pool.reference_append(bt, have, Ls, k, v)
+                pool.assert_equal()
+                if step == 1:
+                    off = np.concatenate([[0], np.cumsum(Ls)])
+                    ref = []
+                    for r in range(B):
+                        if Ls[r] == 0:
+                            ref.append(None)
+                            continue
+                        T = int(have[r] + Ls[r])
+                        Kd = oracle.fp8_dequant_request(pool.h_k, pool.h_ks, bt[r], T, P)
+                        Vd = oracle.fp8_dequant_request(pool.h_v, pool.h_vs, bt[r], T, P)
+                        ref.append(oracle.attn_oracle_request(W.bf16_bits_to_f64(q[off[r]:off[r + 1]]), Kd, Vd, int(have[r]), int(Ls[r]), scale))
+                    mx, mean = errs(from_dev_bits(out), ref, off)
+                    assert mx <= TOL_BF16[0] and mean <= TOL_BF16[1], f"case {case}: {mx:.2e} {mean:.2e}"
+            have = (have + Ls).astype(np.int32)
+        del pool
+
+
 def _replay_on_gpu(tr, **kw):
     Hq, Hkv, d, P = tr.Hq, tr.Hkv, tr.d, tr.P
     pool = Fp8Pool(tr.num_pages, Hq, Hkv, d, P, 1.0 / np.sqrt(d))
