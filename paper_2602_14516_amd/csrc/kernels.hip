@@ -16,6 +16,9 @@
 // and the bf16 P^T operand of the second product is built from the same registers without
 // leaving the register file.  The V^T operand needs 4 consecutive keys per lane for a
 // fixed d; ds_read_b64_tr_b16 delivers exactly that from [key][d] data in LDS.
+// Narrow items of at most 16 query rows (a decode row's grouped heads) use the same formulation on
+// v_mfma_f32_16x16x32_bf16 tiles (lane l owns column q = l % 16 and keys 4 (l/16) + i, 16 + 4 (l/16) + i):
+// half the matrix and softmax work per key of the 32-row tiles, most of which would be padding there.
 //
 // LDS tile layout ("groups"): keys are stored in groups of KPW = 64 / (d/8) keys (4 for
 // d = 128), one group = exactly the 1 KB that one wave-wide 16-byte-per-lane load delivers.
@@ -284,6 +287,104 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
 }
 
 // ---------------------------------------------------------------------------------------------
+// The same steps for a wave of at most 16 query rows (a decode row's grouped heads), with v_mfma_f32_16x16x32_bf16:
+// half the matrix and softmax work of the 32-row steps per key.  A lane owns query column lane % 16; with g = lane / 16
+// it holds S^T for keys 4 g + i and 16 + 4 g + i (i < 4) of the block, which are also its eight k-slots of the second
+// product, so P^T is again built in registers; O^T tile dt holds d = 16 dt + 4 g + i.
+
+__device__ __forceinline__ float max_xor16(float x) {      // as max_xor32, for lane ^ 16
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float sum_xor16(float x) {
+    const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D>
+struct WaveAcc16 {
+    f32x4 O[D / 16];
+    float m;
+    float l;      // this lane's share of the running sum (the four lanes of a column hold quarters)
+};
+
+template <int D>
+__device__ __forceinline__ void qk16(uint32_t kl, const bf16x8 (&Q)[D / 32], f32x4 (&S)[2], int lane) {
+    using G_ = Geo<D>;
+    const int r = lane & 15, g = lane >> 4;
+    // chunk 4*kk + g of key 16*t + r
+    const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
+    constexpr int K16 = (16 / G_::KPW) * G_::GS;
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+        S[t] = f32x4{0, 0, 0, 0};
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) {
+            const u32x4 raw = *LDS_PTR(const u32x4, ka + t * K16 + kk * (G_::KPW * 64));
+            S[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, raw), Q[kk], S[t], 0, 0, 0);
+        }
+    }
+}
+
+// rel: per lane, (last visible key of this lane's query) - (first key of the block) - 4*(lane/16)
+__device__ __forceinline__ void mask16(f32x4 (&S)[2], int rel) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) S[t][i] = 16 * t + i <= rel ? S[t][i] : NEG_INF;
+}
+
+template <int D>
+__device__ __forceinline__ void raise_reference16(WaveAcc16<D>& st, float mx) {
+    const float m_new = fmaxf(st.m, mx);
+    const float alpha = fast_exp2(st.m - (m_new == NEG_INF ? 0.0f : m_new));
+    st.l *= alpha;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) st.O[dt] *= alpha;
+    st.m = m_new;
+}
+
+template <int D>
+__device__ __forceinline__ void pv16(uint32_t vl, const bf16x8& P, WaveAcc16<D>& st, int lane) {
+    using G_ = Geo<D>;
+    const int g = lane >> 4, i16 = lane & 15;
+    // the 16 lanes of a transpose read address 4 keys (4*g + i16/4) x 16 consecutive d and receive 4 keys of one d each
+    const int key = 4 * g + (i16 >> 2);
+    const uint32_t va = vl + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + (i16 & 3) * 8;
+    constexpr int K16 = (16 / G_::KPW) * G_::GS;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) {
+        const uint32_t a0 = va + (dt >> 1) * (G_::KPW * 64) + (dt & 1) * 32;
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0));
+        const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(LDS_PTR(s16x4, a0 + K16));
+        const s16x8 av = {lo[0], lo[1], lo[2], lo[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+        st.O[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, av), P, st.O[dt], 0, 0, 0);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void block16(uint32_t kl, uint32_t vl, const bf16x8 (&Q)[D / 32], WaveAcc16<D>& st,
+                                        float c, int rel, bool masked, int lane) {
+    f32x4 S[2];
+    qk16<D>(kl, Q, S, lane);
+    if (masked) mask16(S, rel);                          // wave-uniform
+    float mx = fmaxf(fmaxf(fmaxf(S[0][0], S[0][1]), fmaxf(S[0][2], S[0][3])), fmaxf(fmaxf(S[1][0], S[1][1]), fmaxf(S[1][2], S[1][3])));
+    mx = max_xor32(max_xor16(mx)) * c;
+    if (__any(mx > st.m + RESCALE_SLACK)) raise_reference16<D>(st, mx);
+    const float m_use = st.m == NEG_INF ? 0.0f : st.m;
+    bf16x8 P;
+    float psum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float pv = fast_exp2(__builtin_fmaf(S[i >> 2][i & 3], c, -m_use));
+        psum += pv;
+        P[i] = (__bf16)pv;
+    }
+    st.l += psum;
+    pv16<D>(vl, P, st, lane);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Software-pipelined processing of one LDS stage by one wave, at 32-key granularity.
 //
 // On this device the vector instructions of the softmax hide behind matrix instructions mostly when both come
@@ -416,6 +517,23 @@ __device__ __forceinline__ void load_q(const AttnParams& p, const ItemCtx& ic, i
     } else {
 #pragma unroll
         for (int kk = 0; kk < Geo<D>::NKK; ++kk) Q[kk] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
+    }
+}
+
+// The same for a wave of 16 rows: lane holds row lane%16, d = kk*32 + (lane/16)*8 .. +8.
+template <int D>
+__device__ __forceinline__ void load_q16(const AttnParams& p, const ItemCtx& ic, int tok, int head_in_group,
+                                         bool valid, int lane, bf16x8 (&Q)[D / 32]) {
+    const int g = lane >> 4;
+    if (valid) {
+        const int hq = ic.kvh * (p.Hq / p.Hkv) + ic.g0 + head_in_group;
+        const char* src = static_cast<const char*>(p.q) + (((int64_t)(ic.row_off + tok) * p.Hq + hq) * D + g * 8) * 2;
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk)
+            Q[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(src + kk * 64));
+    } else {
+#pragma unroll
+        for (int kk = 0; kk < D / 32; ++kk) Q[kk] = __builtin_bit_cast(bf16x8, u32x4{0, 0, 0, 0});
     }
 }
 
@@ -790,22 +908,30 @@ __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic
 // narrow body: <= 32 query rows; the 8 waves take 32-key blocks round-robin, each through its
 // own LDS region, and merge their (m, l, O) through LDS at the end
 
-template <int D, int KVT>
+// ROWS: query rows a wave carries (32, or 16 for items of at most 16 rows: half the matrix and softmax work per key)
+template <int D, int KVT, int ROWS>
 __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem, int tid) {
     using G_ = Geo<D>;
+    constexpr bool R16 = ROWS == 16;
     const int lane = tid & 63, wave = tid >> 6;
-    const int row = lane & 31;
+    const int row = lane & (ROWS - 1);
     const int tl = row / ic.gn, hg = row - tl * ic.gn;
     const bool valid = tl < ic.nq;
     const int tok = ic.q0 + tl;
     const int lim = valid ? ic.C + tok : 0x3fffffff;
     const int first_lim = ic.C + ic.q0;                  // smallest last-visible key among the rows
 
-    bf16x8 Q[G_::NKK];
-    load_q<D>(p, ic, tok, hg, valid, lane, Q);
-    WaveAcc<D> st;
+    bf16x8 Q[R16 ? D / 32 : G_::NKK];
+    std::conditional_t<R16, WaveAcc16<D>, WaveAcc<D>> st;
+    if constexpr (R16) {
+        load_q16<D>(p, ic, tok, hg, valid, lane, Q);
 #pragma unroll
-    for (int db = 0; db < G_::NDB; ++db) st.O[db] = f32x16{0};
+        for (int dt = 0; dt < D / 16; ++dt) st.O[dt] = f32x4{0, 0, 0, 0};
+    } else {
+        load_q<D>(p, ic, tok, hg, valid, lane, Q);
+#pragma unroll
+        for (int db = 0; db < G_::NDB; ++db) st.O[db] = f32x16{0};
+    }
     st.m = NEG_INF;
     st.l = 0.0f;
 
@@ -825,27 +951,34 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             ld.fetch_kv(p, ic, kbase + 32 * ATTN_WAVES, lane);
             if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
         }
-        const int rel = lim - kbase - 4 * (lane >> 5);
-        block32<D>(kl, vl, Q, st, p.c_log2, rel, kbase + 31 > first_lim, lane);
+        if constexpr (R16)
+            block16<D>(kl, vl, Q, st, p.c_log2, lim - kbase - 4 * (lane >> 4), kbase + 31 > first_lim, lane);
+        else
+            block32<D>(kl, vl, Q, st, p.c_log2, lim - kbase - 4 * (lane >> 5), kbase + 31 > first_lim, lane);
     }
     // merge the waves: LDS holds O as [wave][row 0..31][D + 4] fp32 and (m, l) as [wave][32][2]
-    const float ltot = sum_xor32(st.l);
+    const float ltot = R16 ? sum_xor32(sum_xor16(st.l)) : sum_xor32(st.l);
     __syncthreads();                                      // every wave is done with its K/V region
     constexpr int NW = ATTN_WAVES;
     constexpr int OSTR = D + 4;
     const uint32_t obase = smem;
     const uint32_t mlbase = smem + NW * 32 * OSTR * 4;
     {
-        const int g = lane >> 5;
+        const int g = lane / ROWS;
         const uint32_t orow = obase + ((wave * 32 + row) * OSTR) * 4;
+        if constexpr (R16) {
 #pragma unroll
-        for (int db = 0; db < G_::NDB; ++db)
+            for (int dt = 0; dt < D / 16; ++dt) *LDS_PTR(f32x4, orow + (dt * 16 + g * 4) * 4) = st.O[dt];
+        } else {
 #pragma unroll
-            for (int i4 = 0; i4 < 4; ++i4) {
-                const int d0 = db * 32 + i4 * 8 + g * 4;
-                f32x4 o = {st.O[db][i4 * 4], st.O[db][i4 * 4 + 1], st.O[db][i4 * 4 + 2], st.O[db][i4 * 4 + 3]};
-                *LDS_PTR(f32x4, orow + d0 * 4) = o;
-            }
+            for (int db = 0; db < G_::NDB; ++db)
+#pragma unroll
+                for (int i4 = 0; i4 < 4; ++i4) {
+                    const int d0 = db * 32 + i4 * 8 + g * 4;
+                    f32x4 o = {st.O[db][i4 * 4], st.O[db][i4 * 4 + 1], st.O[db][i4 * 4 + 2], st.O[db][i4 * 4 + 3]};
+                    *LDS_PTR(f32x4, orow + d0 * 4) = o;
+                }
+        }
         if (g == 0) {
             *LDS_PTR(float, mlbase + ((wave * 32 + row) * 2) * 4) = st.m;
             *LDS_PTR(float, mlbase + ((wave * 32 + row) * 2 + 1) * 4) = ltot;
@@ -987,8 +1120,12 @@ __device__ __forceinline__ void run_item(const AttnParams& p, int idx, uint32_t 
     const ItemCtx ic = load_item(p, idx);
     if (kind == KIND_WIDE)
         wide_body<D, KVT>(p, ic, smem, tid);
-    else if (kind == KIND_NARROW)
-        narrow_body<D, KVT>(p, ic, smem, tid);
+    else if (kind == KIND_NARROW) {
+        if (ic.nq * ic.gn <= 16)
+            narrow_body<D, KVT, 16>(p, ic, smem, tid);
+        else
+            narrow_body<D, KVT, 32>(p, ic, smem, tid);
+    }
     else if (KVT == KV_BF16)
         append_body(p, ic, D, tid);
 }

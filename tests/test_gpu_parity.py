@@ -55,6 +55,32 @@ def test_small_shapes_elementwise(name, C, L, Hq, Hkv, d, P):
     compare(db.b, out, label=name)
 
 
+def test_narrow_items_of_every_row_count():
+    """Items of at most 32 query rows (tokens x grouped heads) take the streaming path, in two shapes: up to 16 rows on
+    16-row matrix tiles, 17 to 32 rows on 32-row tiles.  Every row count that group sizes 1, 2, 3, 4, 5, 8, 16 and
+    1 to 6 new tokens give is run, with several requests per batch (chunks of more than one token cross the causal
+    diagonal inside a 32-key block; context lengths around block and page boundaries; one batch with forced key splits),
+    for both head dims."""
+    seen = set()
+    case = 0
+    for d in (128, 64):
+        for G in (1, 2, 3, 4, 5, 8, 16):
+            Ls = [l for l in (1, 2, 3, 4, 5, 6) if l * G <= 32]
+            for splits in (0, 3):
+                C = [0, 1, 31, 32, 33, 100, 257, 1000][:len(Ls) + 2]
+                L = (Ls + Ls)[:len(C)]
+                print(f"case {case}: d={d} G={G} C={C} L={L} splits={splits}", flush=True)
+                db = DevBatch(W.make_batch(C, L, 2 * G, 2, d, 16, seed=300 + case, poison=True))
+                out = run_attn(db, fn=A.mixed_batch_attn, force_kv_splits=splits)
+                check_append(db)
+                compare(db.b, out, label=f"narrow rows case {case}")
+                items = A.plan_items(db.cache, db.b.ctx_len, db.b.incr_len, db.b.block_table.shape[1], force_kv_splits=splits)
+                assert (items[items[:, 1] != 3][:, 1] == 1).all()             # every attention item is a narrow one
+                seen |= {int(t * g) for t, g in items[items[:, 1] == 1][:, [6, 4]]}
+                case += 1
+    assert {1, 2, 3, 4, 5, 6, 8, 9, 10, 12, 15, 16, 18, 20, 24, 25, 30, 32} <= seen, sorted(seen)
+
+
 def test_seeded_random_shapes_elementwise():
     """Sixteen seeded random batches: head geometry, page size, head dim, request count and lengths drawn at random,
     with lengths biased towards the boundaries of pages (16 / 32), 32-key blocks, 64-key units and 128-key stages.
