@@ -289,8 +289,8 @@ __device__ __forceinline__ void block32(uint32_t kl, uint32_t vl, const bf16x8 (
 // ---------------------------------------------------------------------------------------------
 // The same steps for a wave of at most 16 query rows (a decode row's grouped heads), with v_mfma_f32_16x16x32_bf16:
 // half the matrix and softmax work of the 32-row steps per key.  A lane owns query column lane % 16; with g = lane / 16
-// it holds S^T for keys 4 g + i and 16 + 4 g + i (i < 4) of the block, which are also its eight k-slots of the second
-// product, so P^T is again built in registers; O^T tile dt holds d = 16 dt + 4 g + i.
+// it holds S^T for keys 4 k + i and 16 + 4 k + i (i < 4; k = key_group16(g)) of the block, which are also its eight k-slots
+// of the second product, so P^T is again built in registers; O^T tile dt holds d = 16 dt + 4 g + i.
 
 __device__ __forceinline__ float max_xor16(float x) {      // as max_xor32, for lane ^ 16
     const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -300,6 +300,11 @@ __device__ __forceinline__ float sum_xor16(float x) {
     const u32x2 r = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
+
+// Which group of 4 keys (of the 16 keys of a tile) the lanes 16 g .. 16 g + 15 hold: 0, 2, 1, 3.  With this order the 32 lanes
+// that one pass of a transpose read serves (g = 0, 1 or g = 2, 3) touch 256 contiguous bytes of the padded key groups
+// (keys 0-3 and 8-11, or 4-7 and 12-15: LDS groups 16 bytes apart modulo 256): no bank conflicts for d = 128.
+__device__ __forceinline__ int key_group16(int g) { return ((g & 1) << 1) | ((g >> 1) & 1); }
 
 template <int D>
 struct WaveAcc16 {
@@ -311,7 +316,9 @@ struct WaveAcc16 {
 template <int D>
 __device__ __forceinline__ void qk16(uint32_t kl, const bf16x8 (&Q)[D / 32], f32x4 (&S)[2], int lane) {
     using G_ = Geo<D>;
-    const int r = lane & 15, g = lane >> 4;
+    // matrix row rho = lane % 16 carries key 4 * key_group16(rho / 4) + rho % 4 of the tile, so that lane group g ends up
+    // with the keys of group key_group16(g)
+    const int r = key_group16((lane & 15) >> 2) * 4 + (lane & 3), g = lane >> 4;
     // chunk 4*kk + g of key 16*t + r
     const uint32_t ka = kl + (r / G_::KPW) * G_::GS + (r % G_::KPW) * 64 + g * 16;
     constexpr int K16 = (16 / G_::KPW) * G_::GS;
@@ -326,7 +333,7 @@ __device__ __forceinline__ void qk16(uint32_t kl, const bf16x8 (&Q)[D / 32], f32
     }
 }
 
-// rel: per lane, (last visible key of this lane's query) - (first key of the block) - 4*(lane/16)
+// rel: per lane, (last visible key of this lane's query) - (first key of the block) - 4*key_group16(lane/16)
 __device__ __forceinline__ void mask16(f32x4 (&S)[2], int rel) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
@@ -348,8 +355,8 @@ template <int D>
 __device__ __forceinline__ void pv16(uint32_t vl, const bf16x8& P, WaveAcc16<D>& st, int lane) {
     using G_ = Geo<D>;
     const int g = lane >> 4, i16 = lane & 15;
-    // the 16 lanes of a transpose read address 4 keys (4*g + i16/4) x 16 consecutive d and receive 4 keys of one d each
-    const int key = 4 * g + (i16 >> 2);
+    // the 16 lanes of a transpose read address 4 keys x 16 consecutive d and receive 4 keys of one d each
+    const int key = 4 * key_group16(g) + (i16 >> 2);
     const uint32_t va = vl + (key / G_::KPW) * G_::GS + (key % G_::KPW) * 64 + (i16 & 3) * 8;
     constexpr int K16 = (16 / G_::KPW) * G_::GS;
 #pragma unroll
@@ -952,7 +959,7 @@ __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& 
             if (b + 2 * ATTN_WAVES < nblocks) ld.fetch_pages(p, ic, kbase + 64 * ATTN_WAVES, lane);
         }
         if constexpr (R16)
-            block16<D>(kl, vl, Q, st, p.c_log2, lim - kbase - 4 * (lane >> 4), kbase + 31 > first_lim, lane);
+            block16<D>(kl, vl, Q, st, p.c_log2, lim - kbase - 4 * key_group16(lane >> 4), kbase + 31 > first_lim, lane);
         else
             block32<D>(kl, vl, Q, st, p.c_log2, lim - kbase - 4 * (lane >> 5), kbase + 31 > first_lim, lane);
     }
