@@ -811,7 +811,7 @@ template <int D, int KVT>
 __device__ __forceinline__ void wide_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem, int tid) {
     using G_ = Geo<D>;
     constexpr bool DMA = KVT == KV_BF16;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int tqw = 32 / ic.gn;                            // tokens per wave
     const int row = lane & 31;
     const int tl = row / ic.gn, hg = row - tl * ic.gn;
@@ -920,7 +920,7 @@ template <int D, int KVT, int ROWS>
 __device__ __forceinline__ void narrow_body(const AttnParams& p, const ItemCtx& ic, uint32_t smem, int tid) {
     using G_ = Geo<D>;
     constexpr bool R16 = ROWS == 16;
-    const int lane = tid & 63, wave = tid >> 6;
+    const int lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int row = lane & (ROWS - 1);
     const int tl = row / ic.gn, hg = row - tl * ic.gn;
     const bool valid = tl < ic.nq;
