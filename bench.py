@@ -508,6 +508,9 @@ def main():
         print("bench.py: this build measures one GPU only (no collectives, no sharding); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # runs what is built; builds only what is missing (a fresh checkout)
+
     if args.only == "simulate":
         # host only: the serving simulator on the fitted cost model, three routing policies x reordering on / off
         from paper_2602_14516_amd import simulator as S

@@ -10,6 +10,9 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
+    # the tests run the libraries that are built; in a fresh checkout nothing is, and importing the package would raise
+    import __graft_entry__
+    __graft_entry__.ensure_built()
 
 
 def _have_gpu():
