@@ -372,6 +372,28 @@ def chunked_local_prefill(torch, A, W):
     return {"only": "chunked", "decode_step_alone_ms": dec, "runs": out}
 
 
+def stream_per_cu(torch, A, W):
+    """Streaming rate of whole-row decode items against the number of CUs that stream at once: b rows of 16 384 cached
+    tokens, 8 KV heads, one work item per (row, KV head) (`force_kv_splits=1` keeps the rows whole), bf16 and 8-bit cache."""
+    sh = W.CONFIG_SHAPES[3]
+    out = []
+    for fp8 in (False, True):
+        for rows in (2, 8, 16, 24, 32, 64):
+            C, L = np.full(rows, 16384, np.int32), np.ones(rows, np.int32)
+            db = device_batch(torch, A, W, C, L, sh, seed=1, fp8=fp8)
+            ws = torch.empty(max(A.workspace_bytes(db["cache"], C, L, db["bt"].shape[1], force_kv_splits=1), 256), dtype=torch.uint8, device="cuda")
+            fn = lambda: A.mixed_batch_attn(db["cache"], C, L, db["bt"], db["q"], db["k_new"], db["v_new"], out=db["out"], workspace=ws,
+                                            force_kv_splits=1)
+            time_calls(torch, fn, 20, 10)
+            a, _, _ = kernel_times(torch, A, fn, 3)
+            by = rows * 16385 * sh["Hkv"] * sh["d"] * (1 if fp8 else 2) * 2
+            items = rows * sh["Hkv"]
+            out.append({"cache": "8-bit" if fp8 else "bf16", "rows": rows, "items": items, "attn_kernel_ms": a, "GBps": by / a / 1e6,
+                        "GBps_per_streaming_CU": by / a / 1e6 / min(256, items)})
+            del db, ws
+    return {"only": "percu", "keys_per_row": 16384, "runs": out}
+
+
 def kv_transfer(torch, A, W):
     """Pack / unpack of a KV transfer (paper Section 3, T_kv; Eq. 2): the history KV of 16 requests
     (configuration-2 shape, 77 k tokens) for one destination rank's share of 2 of the 8 KV heads, and for all
@@ -501,7 +523,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=50)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-mixed", action="store_true")
-    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'decode_fp8' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'simulate' | 'cfg4' | 'datadep' steps, or "
+    ap.add_argument("--only", default="", help="profiling aid: run only 'prefill' | 'decode' | 'decode_fp8' | 'mixed' | 'prefill3' | 'trace' | 'model' | 'chunked' | 'kvtransfer' | 'percu' | 'simulate' | 'cfg4' | 'datadep' steps, or "
                     "'copycal' (a plain 1 GiB device copy, to calibrate the FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -536,6 +558,10 @@ def main():
 
     if args.only == "kvtransfer":
         print(json.dumps(kv_transfer(torch, A, W)))
+        return
+
+    if args.only == "percu":
+        print(json.dumps(stream_per_cu(torch, A, W)))
         return
 
     if args.only == "chunked":
